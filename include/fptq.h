@@ -1,0 +1,119 @@
+/*
+ * fptq -- statically quantized INT4-weight x INT4-activation linear layer for AMD MI355X (gfx950).
+ *
+ * The library implements the run-time side of FPTQuant's quantized linear map:
+ *
+ *     x~_t   = S_t * x_t                         per-token scale,            Sec. 3.1.3 (Step 1)
+ *     q_t,k  = clamp(rne(x~_t,k / s_a), -8, 7)   static per-tensor INT4,     App. B "Static quantization"
+ *     acc_t,o = sum_k q_t,k * w_o,k              INT32 accumulation,         App. J "Setup"
+ *     y_t,o  = bf16(acc_t,o * s_a * s_w[o])      float scales after the
+ *                                                integer matmul,             App. B "Static quantization"
+ *
+ * with 4-bit operands stored two per byte (App. J).  The mergeable transforms of Sec. 3.1.1 and
+ * 3.1.2 are folded into the weights offline and never appear here.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every tensor pointer is a DEVICE pointer; scalars are passed by value.
+ *   - The caller owns all memory.  Entry points without "_static" in their name allocate nothing,
+ *     never synchronise, and enqueue their kernels on `stream` (a hipStream_t; NULL = the null stream).
+ *   - Every function returns 0 (FPTQ_OK) or a negative FPTQ_ERR_* code; arguments are validated
+ *     before anything is launched, so a failed call writes nothing.  fptq_last_error() returns a
+ *     thread-local description of the last failure.
+ *   - X is [M x K] bf16 row-major (tokens x in-features).  W is [N x K] (out x in).  Y is [M x N]
+ *     bf16 row-major.  Any M, N, K >= 1 is accepted (M*K, N*K, M*N < 2^40).
+ *
+ * Packed INT4 layout (the same for activations and weights, produced only by this library):
+ *   K is cut into tiles of 128 values (64 bytes); the buffer holds, tile after tile, one 64-byte
+ *   segment per row:   byte(row, k) = ((k / 128) * rows + row) * 64 + (k % 128) / 2,
+ *   value k in the low nibble when k is even, the high nibble when odd, two's complement.
+ *   K is padded to a multiple of 128 with zeros.  fptq_packed_bytes() gives the buffer size.
+ *   fptq_unpack() converts back to one int8 per value, so callers never depend on this layout.
+ */
+#ifndef FPTQ_H
+#define FPTQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FPTQ_OK 0
+#define FPTQ_ERR_NULL (-1)  /* a required pointer is NULL                          */
+#define FPTQ_ERR_SHAPE (-2) /* M, N or K is < 1 or too large                       */
+#define FPTQ_ERR_SIZE (-3)  /* a buffer size passed by the caller is too small     */
+#define FPTQ_ERR_MODE (-4)  /* unknown scale mode, or its arguments are missing    */
+#define FPTQ_ERR_HIP (-5)   /* the HIP runtime refused a launch (see last_error)   */
+#define FPTQ_ERR_VALUE (-6) /* a scalar is not usable (s_a not finite or <= 0)     */
+#define FPTQ_ERR_ALIGN (-7) /* a pointer is misaligned: packed buffers, y_bf16 and
+                               acc_dbg need 16 bytes, fp32 vectors 4, x_bf16 2     */
+
+/* How fptq_quantize_act obtains the per-token scale S_t (Sec. 3.1.3). */
+#define FPTQ_SCALE_NONE 0  /* S_t = 1                                                          */
+#define FPTQ_SCALE_RMS 1   /* S_t = 1 / sqrt(mean_k x_t,k^2 + eps): what the block's RMSNorm computes */
+#define FPTQ_SCALE_GIVEN 2 /* S_t = row_scale_in[t]: the S_n carried by the recursion of Eq. (6)-(7)  */
+
+int fptq_version(void);
+const char *fptq_last_error(void);
+
+/* Bytes of a packed [rows x K] INT4 buffer in the library layout; negative FPTQ_ERR_SHAPE if
+ * rows < 1 or K < 1. */
+int64_t fptq_packed_bytes(int64_t rows, int64_t K);
+
+/*
+ * Offline: pack INT4 weights (App. J double-packed storage).
+ *   w_int          device, int8 [N x K] row-major, one value per byte; only the low nibble is kept,
+ *                  so values outside [-8, 7] are a caller error.
+ *   w_packed       device, at least fptq_packed_bytes(N, K) bytes (w_packed_bytes is checked).
+ * The packed blob serves both the prefill and the decode kernels.
+ */
+int fptq_pack_weights(const int8_t *w_int, int64_t N, int64_t K, void *w_packed, int64_t w_packed_bytes,
+                      void *stream);
+
+/*
+ * Per-token scale + static quantization + packing of the activations, one pass over X
+ * (Sec. 3.1.3 Step 1; App. B static quantization; App. J storage).
+ *   x_bf16         device, bf16 [M x K] row-major (leading dimension K)
+ *   scale_mode     FPTQ_SCALE_*; eps is used by RMS only; row_scale_in [M] fp32 is required by GIVEN
+ *   s_a            static activation scale (> 0, finite), fixed by calibration ahead of time
+ *   xq_packed      device, at least fptq_packed_bytes(M, K) bytes (xq_bytes is checked)
+ *   row_scale_out  device, fp32 [M] or NULL: receives S_t (1 for NONE), e.g. to continue the
+ *                  recursion or to undo the scale later
+ * Arithmetic: sum of squares in fp64; S_t = (float)(1 / sqrt(ss / K + eps)); c_t = S_t * (1.0f / s_a)
+ * in fp32; q = clamp(rne((float)x * c_t), -8, 7); NaN quantizes to 0, +-Inf to 7 / -8.
+ */
+int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, float eps,
+                      const float *row_scale_in, float s_a, void *xq_packed, int64_t xq_bytes,
+                      float *row_scale_out, void *stream);
+
+/*
+ * The quantized linear layer proper: INT4 x INT4 matmul with INT32 accumulation and the
+ * float-scale epilogue (App. J; App. B).  Picks a few-token (bandwidth-bound) kernel for small M
+ * and the INT8-MFMA GEMM otherwise.
+ *   xq_packed      device, packed activations [M x K] from fptq_quantize_act
+ *   w_packed       device, packed weights [N x K] from fptq_pack_weights
+ *   s_a            the same static activation scale given to fptq_quantize_act
+ *   s_w            device, fp32 [N]: per-output-channel weight scales
+ *   row_out_scale  device, fp32 [M] or NULL: optional extra per-token factor d_t on the output
+ *                  (NULL leaves the output in the scaled representation Y~ = S * Y of Eq. (5))
+ *   y_bf16         device, bf16 [M x N] row-major
+ *   acc_dbg        device, int32 [M x N] or NULL: when given, also receives the exact integer
+ *                  accumulators (for parity checks; leave NULL in timed runs)
+ * Epilogue arithmetic (fp32): y = bf16_rne((float)acc * (s_a * s_w[o]) [* d_t]).
+ */
+int fptq_w4a4_linear(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                     const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream);
+
+/* Same contract as fptq_w4a4_linear but always runs the simple one-thread-per-output kernel
+ * (no MFMA, no LDS).  A second, independent GPU implementation used by the tests to cross-check
+ * the tuned kernels at full size. */
+int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                         const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream);
+
+/* Library layout -> one int8 per value, [rows x K] row-major (for parity checks and debugging). */
+int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FPTQ_H */

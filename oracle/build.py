@@ -7,7 +7,7 @@ SRC = os.path.join(HERE, "fptq_oracle.c")
 LIB = os.path.join(HERE, "liboracle.so")
 
 # -ffp-contract=off: the quantizer's single fp32 multiply must not be fused with anything.
-CFLAGS = ["-O3", "-march=native", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
+CFLAGS = ["-O3", "-march=x86-64-v3", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 
 def build(force: bool = True) -> str:

@@ -26,7 +26,7 @@
  *     y = bf16 round-to-nearest-even of yf
  * Canonical packing: byte j of a row = (v[2j] & 15) | ((v[2j+1] & 15) << 4).
  *
- * Build: gcc -O3 -march=native -ffp-contract=off -fopenmp -shared -fPIC
+ * Build: gcc -O3 -march=x86-64-v3 -ffp-contract=off -fopenmp -shared -fPIC
  */
 #include <math.h>
 #include <stdint.h>

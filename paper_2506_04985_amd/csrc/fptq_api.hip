@@ -1,0 +1,177 @@
+// C ABI of the fptq library: argument validation, shape dispatch, error text.
+// Every entry point validates first and launches afterwards, so a failing call writes nothing.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "fptq_common.h"
+
+namespace fptq {
+
+static thread_local char g_err[256] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+static int hip_fail(const char *what, hipError_t e)
+{
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return FPTQ_ERR_HIP;
+}
+
+static const int64_t MAX_ELEMS = (int64_t)1 << 40;
+
+static int check_dims(const char *fn, int64_t a, int64_t b, const char *an, const char *bn)
+{
+    if (a < 1 || b < 1 || a > MAX_ELEMS / b) {
+        set_error("%s: bad shape %s=%lld %s=%lld", fn, an, (long long)a, bn, (long long)b);
+        return FPTQ_ERR_SHAPE;
+    }
+    return FPTQ_OK;
+}
+
+static int check_align(const char *fn, const void *p, unsigned a, const char *name)
+{
+    if (reinterpret_cast<uintptr_t>(p) & (a - 1)) {
+        set_error("%s: %s must be %u-byte aligned", fn, name, a);
+        return FPTQ_ERR_ALIGN;
+    }
+    return FPTQ_OK;
+}
+
+// Largest M served by the few-token kernel; above it the MFMA GEMM runs.
+static const int64_t DECODE_MAX_M = 32;
+
+typedef hipError_t (*linear_fn)(const uint8_t *, const uint8_t *, int64_t, int64_t, int64_t, float, const float *,
+                                const float *, uint16_t *, int32_t *, hipStream_t);
+
+static int linear_common(const char *fn, linear_fn force, const void *xq, const void *wq, int64_t M, int64_t N,
+                         int64_t K, float s_a, const float *s_w, const float *d, void *y, int32_t *acc, void *stream)
+{
+    if (!xq || !wq || !s_w || !y) {
+        set_error("%s: NULL pointer", fn);
+        return FPTQ_ERR_NULL;
+    }
+    int rc;
+    if ((rc = check_dims(fn, M, K, "M", "K")) || (rc = check_dims(fn, N, K, "N", "K")) ||
+        (rc = check_dims(fn, M, N, "M", "N")))
+        return rc;
+    if (!(s_a > 0.0f) || !std::isfinite(s_a)) {
+        set_error("%s: s_a must be finite and > 0", fn);
+        return FPTQ_ERR_VALUE;
+    }
+    if ((rc = check_align(fn, xq, 16, "xq_packed")) || (rc = check_align(fn, wq, 16, "w_packed")) ||
+        (rc = check_align(fn, y, 16, "y_bf16")) || (rc = check_align(fn, acc, 16, "acc_dbg")) ||
+        (rc = check_align(fn, s_w, 4, "s_w")) || (rc = check_align(fn, d, 4, "row_out_scale")))
+        return rc;
+    linear_fn f = force ? force : (M <= DECODE_MAX_M ? launch_linear_decode : launch_linear_mfma);
+    hipError_t e = f((const uint8_t *)xq, (const uint8_t *)wq, M, N, K, s_a, s_w, d, (uint16_t *)y, acc,
+                     (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
+}
+
+}  // namespace fptq
+
+using namespace fptq;
+
+extern "C" {
+
+int fptq_version(void) { return 100; }
+
+const char *fptq_last_error(void) { return g_err; }
+
+int64_t fptq_packed_bytes(int64_t rows, int64_t K)
+{
+    if (check_dims("fptq_packed_bytes", rows, K, "rows", "K")) return FPTQ_ERR_SHAPE;
+    return packed_bytes(rows, K);
+}
+
+int fptq_pack_weights(const int8_t *w_int, int64_t N, int64_t K, void *w_packed, int64_t w_packed_bytes, void *stream)
+{
+    if (!w_int || !w_packed) {
+        set_error("fptq_pack_weights: NULL pointer");
+        return FPTQ_ERR_NULL;
+    }
+    int rc = check_dims("fptq_pack_weights", N, K, "N", "K");
+    if (rc) return rc;
+    if (w_packed_bytes < packed_bytes(N, K)) {
+        set_error("fptq_pack_weights: buffer of %lld bytes, need %lld", (long long)w_packed_bytes,
+                  (long long)packed_bytes(N, K));
+        return FPTQ_ERR_SIZE;
+    }
+    if ((rc = check_align("fptq_pack_weights", w_packed, 16, "w_packed"))) return rc;
+    hipError_t e = launch_pack_weights(w_int, N, K, (uint8_t *)w_packed, (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_pack_weights", e);
+}
+
+int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, float eps, const float *row_scale_in,
+                      float s_a, void *xq_packed, int64_t xq_bytes, float *row_scale_out, void *stream)
+{
+    if (!x_bf16 || !xq_packed) {
+        set_error("fptq_quantize_act: NULL pointer");
+        return FPTQ_ERR_NULL;
+    }
+    int rc = check_dims("fptq_quantize_act", M, K, "M", "K");
+    if (rc) return rc;
+    if (scale_mode != FPTQ_SCALE_NONE && scale_mode != FPTQ_SCALE_RMS && scale_mode != FPTQ_SCALE_GIVEN) {
+        set_error("fptq_quantize_act: unknown scale_mode %d", scale_mode);
+        return FPTQ_ERR_MODE;
+    }
+    if (scale_mode == FPTQ_SCALE_GIVEN && !row_scale_in) {
+        set_error("fptq_quantize_act: FPTQ_SCALE_GIVEN needs row_scale_in");
+        return FPTQ_ERR_MODE;
+    }
+    if (!(s_a > 0.0f) || !std::isfinite(s_a) || !(eps >= 0.0f)) {
+        set_error("fptq_quantize_act: s_a must be finite and > 0, eps >= 0");
+        return FPTQ_ERR_VALUE;
+    }
+    if (xq_bytes < packed_bytes(M, K)) {
+        set_error("fptq_quantize_act: buffer of %lld bytes, need %lld", (long long)xq_bytes,
+                  (long long)packed_bytes(M, K));
+        return FPTQ_ERR_SIZE;
+    }
+    if ((rc = check_align("fptq_quantize_act", xq_packed, 16, "xq_packed")) ||
+        (rc = check_align("fptq_quantize_act", x_bf16, 2, "x_bf16")) ||
+        (rc = check_align("fptq_quantize_act", row_scale_in, 4, "row_scale_in")) ||
+        (rc = check_align("fptq_quantize_act", row_scale_out, 4, "row_scale_out")))
+        return rc;
+    // the one fp32 division of the quantizer happens here, on the host
+    volatile float inv = 1.0f / s_a;
+    hipError_t e = launch_quantize_act((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv,
+                                       (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_quantize_act", e);
+}
+
+int fptq_w4a4_linear(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                     const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream)
+{
+    return linear_common("fptq_w4a4_linear", nullptr, xq_packed, w_packed, M, N, K, s_a, s_w, row_out_scale, y_bf16,
+                         acc_dbg, stream);
+}
+
+int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                         const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream)
+{
+    return linear_common("fptq_w4a4_linear_ref", launch_linear_ref, xq_packed, w_packed, M, N, K, s_a, s_w,
+                         row_out_scale, y_bf16, acc_dbg, stream);
+}
+
+int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream)
+{
+    if (!packed || !out_int8) {
+        set_error("fptq_unpack: NULL pointer");
+        return FPTQ_ERR_NULL;
+    }
+    int rc = check_dims("fptq_unpack", rows, K, "rows", "K");
+    if (rc) return rc;
+    if ((rc = check_align("fptq_unpack", packed, 16, "packed"))) return rc;
+    hipError_t e = launch_unpack((const uint8_t *)packed, rows, K, out_int8, (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_unpack", e);
+}
+
+}  // extern "C"

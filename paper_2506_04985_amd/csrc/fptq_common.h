@@ -1,0 +1,52 @@
+// Shared declarations of the fptq HIP library (gfx950 only): packed layout arithmetic, error
+// reporting, and the launcher prototypes that tie the translation units together.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fptq.h"
+
+namespace fptq {
+
+// Packed INT4 layout: K is cut into tiles of KT values; each (tile, row) pair owns one
+// 64-byte segment, tiles outermost.  Within a segment value k sits in byte (k % KT) / 2,
+// low nibble first.
+constexpr int KT = 128;          // values per K tile
+constexpr int SEG = KT / 2;      // bytes per (row, tile) segment
+
+__host__ __device__ inline int64_t k_tiles(int64_t K) { return (K + KT - 1) / KT; }
+__host__ __device__ inline int64_t packed_bytes(int64_t rows, int64_t K) { return k_tiles(K) * rows * SEG; }
+
+// error text of the calling thread (set by the API layer)
+void set_error(const char *fmt, ...);
+
+// kernel launchers (each returns a hipError_t from hipGetLastError after the launch)
+hipError_t launch_pack_weights(const int8_t *w, int64_t N, int64_t K, uint8_t *out, hipStream_t s);
+hipError_t launch_unpack(const uint8_t *packed, int64_t rows, int64_t K, int8_t *out, hipStream_t s);
+hipError_t launch_quantize_act(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
+                               float inv_s_a, uint8_t *out, float *row_out, hipStream_t s);
+hipError_t launch_linear_ref(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                             const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s);
+hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                              const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s);
+hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                                const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s);
+
+// fp32 -> bf16 bit pattern, round to nearest even (NaN stays a quiet NaN)
+__device__ inline uint16_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// The dequantizing epilogue of the layer for one output: fp32 throughout, no fused operations.
+__device__ inline uint16_t dequant_bf16(int32_t acc, float cw, const float *d, int64_t t)
+{
+    float yf = (float)acc * cw;
+    if (d) yf = yf * d[t];
+    return bf16_rne(yf);
+}
+
+}  // namespace fptq

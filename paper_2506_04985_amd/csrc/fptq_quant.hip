@@ -1,0 +1,146 @@
+// Activation path of the quantized linear layer: per-token scale (Sec. 3.1.3 Step 1), static
+// per-tensor INT4 quantization (App. B) and nibble packing (App. J) in one pass over X.
+//
+// One workgroup per token row.  The row is read once from HBM and kept in registers while the
+// sum of squares is reduced, then quantized from the registers.  Bandwidth-bound: 2 bytes read
+// and half a byte written per element.
+#include "fptq_common.h"
+
+namespace fptq {
+
+constexpr int QT = 256;        // threads per row
+constexpr int QCHUNK = 8;      // bf16 values per 16-byte load
+constexpr int QREG_CHUNKS = 16; // chunks a thread keeps in registers: rows up to 256*8*16 = 32768 values
+
+__device__ inline float bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
+
+// q = clamp(rne(x * c), -8, 7) as a 4-bit two's complement field; NaN -> 0
+__device__ inline uint32_t quant_nibble(float x, float c)
+{
+    float u = x * c;
+    float r = __builtin_rintf(u);
+    r = fminf(fmaxf(r, -8.0f), 7.0f);
+    int q = (u != u) ? 0 : (int)r;
+    return (uint32_t)q & 15u;
+}
+
+__device__ inline double block_sum(double v, double *lds)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) lds[wave] = v;
+    __syncthreads();
+    double tot = lds[0];
+#pragma unroll
+    for (int w = 1; w < QT / 64; ++w) tot += lds[w];
+    return tot;
+}
+
+__device__ inline void store_word(uint8_t *out, int64_t M, int64_t t, int64_t k0, uint32_t word)
+{
+    *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = word;
+}
+
+// VEC: K is a multiple of 8, so every row starts 16-byte aligned and chunks never straddle K.
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K, float eps,
+                                                          const float *__restrict__ row_in, float inv_s_a,
+                                                          uint8_t *__restrict__ out, float *__restrict__ row_out)
+{
+    __shared__ double red[QT / 64];
+    const int64_t t = blockIdx.x;
+    const uint16_t *row = x + t * K;
+    const int64_t Kpad = k_tiles(K) * KT;
+    const int tid = threadIdx.x;
+
+    uint4 regs[QREG_CHUNKS];
+    const bool in_regs = VEC && K <= (int64_t)QT * QCHUNK * QREG_CHUNKS;
+    if (in_regs) {
+#pragma unroll
+        for (int i = 0; i < QREG_CHUNKS; ++i) {
+            int64_t k0 = ((int64_t)i * QT + tid) * QCHUNK;
+            regs[i] = k0 < K ? *reinterpret_cast<const uint4 *>(row + k0) : make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    float r = 1.0f;
+    if (MODE == FPTQ_SCALE_RMS) {
+        double ss = 0.0;
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < QREG_CHUNKS; ++i) {
+                const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    double a = (double)bf16_to_f32(w[j] & 0xffffu), b = (double)bf16_to_f32(w[j] >> 16);
+                    ss += a * a;
+                    ss += b * b;
+                }
+            }
+        } else {
+            for (int64_t k = tid; k < K; k += QT) {
+                double a = (double)bf16_to_f32(row[k]);
+                ss += a * a;
+            }
+        }
+        ss = block_sum(ss, red);
+        r = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
+    } else if (MODE == FPTQ_SCALE_GIVEN) {
+        r = row_in[t];
+    }
+    const float c = (MODE == FPTQ_SCALE_NONE) ? inv_s_a : r * inv_s_a;
+    if (tid == 0 && row_out) row_out[t] = r;
+
+    if (in_regs) {
+#pragma unroll
+        for (int i = 0; i < QREG_CHUNKS; ++i) {
+            int64_t k0 = ((int64_t)i * QT + tid) * QCHUNK;
+            if (k0 < Kpad) {
+                const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+                uint32_t word = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c) << (8 * j);
+                    word |= quant_nibble(bf16_to_f32(w[j] >> 16), c) << (8 * j + 4);
+                }
+                store_word(out, M, t, k0, k0 < K ? word : 0u);
+            }
+        }
+    } else {
+        for (int64_t k0 = (int64_t)tid * QCHUNK; k0 < Kpad; k0 += (int64_t)QT * QCHUNK) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int i = 0; i < QCHUNK; ++i) {
+                int64_t k = k0 + i;
+                if (k < K) word |= quant_nibble(bf16_to_f32(row[k]), c) << (4 * i);   // K padding stays zero
+            }
+            store_word(out, M, t, k0, word);
+        }
+    }
+}
+
+template <int MODE>
+static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps, const float *row_in, float inv_s_a,
+                              uint8_t *out, float *row_out, hipStream_t s)
+{
+    dim3 grid((unsigned)M), block(QT);
+    if (K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0)
+        quantize_act_kernel<MODE, true><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+    else
+        quantize_act_kernel<MODE, false><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_act(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
+                               float inv_s_a, uint8_t *out, float *row_out, hipStream_t s)
+{
+    if (M > 0x7fffffff) return hipErrorInvalidValue;
+    switch (mode) {
+    case FPTQ_SCALE_NONE: return launch_mode<FPTQ_SCALE_NONE>(x, M, K, eps, row_in, inv_s_a, out, row_out, s);
+    case FPTQ_SCALE_RMS: return launch_mode<FPTQ_SCALE_RMS>(x, M, K, eps, row_in, inv_s_a, out, row_out, s);
+    default: return launch_mode<FPTQ_SCALE_GIVEN>(x, M, K, eps, row_in, inv_s_a, out, row_out, s);
+    }
+}
+
+}  // namespace fptq

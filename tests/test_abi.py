@@ -1,0 +1,45 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and its pure host entry points behave."""
+import ctypes
+import os
+import re
+
+from paper_2506_04985_amd import binding as fptq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "fptq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fptq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = fptq.lib()
+    names = header_symbols()
+    assert set(names) == set(fptq.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_host_only_entry_points():
+    L = fptq.lib()
+    assert L.fptq_version() >= 100
+    assert L.fptq_packed_bytes(1, 1) == 64
+    assert L.fptq_packed_bytes(10, 128) == 640
+    assert L.fptq_packed_bytes(10, 129) == 1280
+    assert L.fptq_packed_bytes(57344, 8192) == 57344 * 8192 // 2
+    assert L.fptq_packed_bytes(0, 8) == -2
+    assert b"bad shape" in L.fptq_last_error()
+    # validation happens before any launch, so these return without touching a device
+    assert L.fptq_pack_weights(None, 4, 4, None, 0, None) == -1
+    assert L.fptq_quantize_act(None, 4, 4, 1, 0.0, None, 1.0, None, 0, None, None) == -1
+    assert L.fptq_unpack(None, 1, 1, None, None) == -1
+    dummy = ctypes.c_void_p(256)
+    assert L.fptq_quantize_act(dummy, 0, 4, 1, 0.0, None, 1.0, dummy, 0, None, None) == -2
+    assert L.fptq_quantize_act(dummy, 4, 4, 9, 0.0, None, 1.0, dummy, 1 << 20, None, None) == -4
+    assert L.fptq_quantize_act(dummy, 4, 4, 1, 0.0, None, -1.0, dummy, 1 << 20, None, None) == -6
+    assert L.fptq_quantize_act(dummy, 4, 4, 1, 0.0, None, 1.0, dummy, 8, None, None) == -3
+    assert L.fptq_w4a4_linear(dummy, dummy, 4, 0, 4, 1.0, dummy, None, dummy, None, None) == -2
+    assert L.fptq_w4a4_linear(dummy, dummy, 4, 4, 4, float("inf"), dummy, None, dummy, None, None) == -6

@@ -1,0 +1,175 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Sizes here are the ones the oracle recomputes whole in seconds: the tiny configuration, ragged
+and degenerate shapes, several tiles plus a tail.  Full-size configurations are in
+test_gpu_configs.py.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_04985_amd import binding as fptq
+from paper_2506_04985_amd import synth
+
+from gpu_util import Y_TOL, dev, dev_bf16, host_bits, layout_from_canonical, run_gpu_linear, y_error
+
+pytestmark = pytest.mark.gpu
+
+
+def small_case(M, N, K, mode, seed=7, dist="normal", count=2, mult=4.0):
+    return synth.LinearCase("t", f"m{M}n{N}k{K}", M, N, K, dist, 0.0, count, mult, mode, seed)
+
+
+# ------------------------------------------------------------------ packing
+@pytest.mark.parametrize("N,K", [(1, 2), (5, 34), (16, 128), (33, 130), (300, 512), (257, 1000), (64, 4096)])
+def test_pack_weights_layout_and_roundtrip(oracle, N, K):
+    rng = np.random.default_rng(N * 1000 + K)
+    w = rng.integers(-8, 8, (N, K), dtype=np.int8)
+    packed = fptq.fptq_pack_weights(dev(w))
+    assert packed.numel() == fptq.fptq_packed_bytes(N, K) == ((K + 127) // 128) * N * 64
+    back = fptq.fptq_unpack(packed, N, K).cpu().numpy()
+    assert np.array_equal(back, w)
+    # the documented byte layout, rebuilt from the oracle's canonical packing
+    want = layout_from_canonical(oracle.pack(w), N, K)
+    assert np.array_equal(packed.cpu().numpy(), want)
+
+
+def test_pack_weights_odd_K():
+    rng = np.random.default_rng(1)
+    w = rng.integers(-8, 8, (7, 129), dtype=np.int8)
+    packed = fptq.fptq_pack_weights(dev(w))
+    assert np.array_equal(fptq.fptq_unpack(packed, 7, 129).cpu().numpy(), w)
+
+
+# ------------------------------------------------------------------ activation quantizer
+@pytest.mark.parametrize("mode", [synth.MODE_NONE, synth.MODE_RMS, synth.MODE_GIVEN])
+@pytest.mark.parametrize("M,K", [(1, 8), (3, 34), (5, 129), (17, 512), (128, 512), (9, 4096), (4, 11008), (2, 28672),
+                                 (2, 40000), (3, 1001)])
+def test_quantize_act_bit_exact(oracle, mode, M, K):
+    case = small_case(M, 8, K, mode, seed=M + K)
+    inp = synth.draw(case, with_weights=False)
+    for eps in (0.0, 1e-5):
+        xq, r = fptq.fptq_quantize_act(dev_bf16(inp.x_bits), float(inp.s_a), mode, eps, dev(inp.row_scale_in))
+        q = fptq.fptq_unpack(xq, M, K).cpu().numpy()
+        r_ref = oracle.row_scale(inp.x_bits, mode, eps, inp.row_scale_in)
+        q_ref = oracle.quantize(inp.x_bits, inp.s_a, None if mode == synth.MODE_NONE else r_ref)
+        assert np.array_equal(r.cpu().numpy().view(np.uint32), r_ref.view(np.uint32))
+        assert np.array_equal(q, q_ref)
+        if M * K >= 512:
+            assert q_ref.min() < 0 < q_ref.max()
+        if K % 2 == 0:   # padded bytes beyond K are zero and the layout is the documented one
+            want = layout_from_canonical(oracle.pack(q_ref), M, K)
+            assert np.array_equal(xq.cpu().numpy(), want)
+
+
+def test_quantize_act_special_values(oracle):
+    """Ties, clamp edges, infinities, NaN, signed zero, subnormals: same decisions as the oracle."""
+    vals = np.array([0.5, 1.5, 2.5, -0.5, -1.5, 7.5, -8.5, 6.5, -7.5, 100.0, -100.0, 0.0, -0.0,
+                     np.inf, -np.inf, np.nan, 1e-40, -1e-40, 3.0, -3.0], np.float32)
+    x = np.zeros((2, 128), np.float32)
+    x[0, :len(vals)] = vals
+    x[1, :len(vals)] = vals * 2
+    bits = synth.f32_to_bf16_bits(x)
+    bits[0, 15] = 0x7FC0
+    for s_a in (1.0, 2.0, 0.37):
+        xq, _ = fptq.fptq_quantize_act(dev_bf16(bits), s_a, synth.MODE_NONE)
+        q = fptq.fptq_unpack(xq, 2, 128).cpu().numpy()
+        assert np.array_equal(q, oracle.quantize(bits, np.float32(s_a), None))
+    # every bf16 bit pattern once, with a row scale
+    allbits = np.arange(65536, dtype=np.uint16).reshape(8, 8192)
+    r = np.array([1.0, 0.5, 0.3333, 2.7, 13.37, 1e-3, 100.0, 7.0], np.float32)
+    xq, r_out = fptq.fptq_quantize_act(dev_bf16(allbits), 0.731, synth.MODE_GIVEN, 0.0, dev(r))
+    q = fptq.fptq_unpack(xq, 8, 8192).cpu().numpy()
+    assert np.array_equal(q, oracle.quantize(allbits, np.float32(0.731), r))
+    assert np.array_equal(r_out.cpu().numpy(), r)
+
+
+# ------------------------------------------------------------------ the linear layer
+SHAPES = [(1, 1, 2), (3, 5, 34), (128, 512, 512), (100, 300, 640), (257, 513, 1024), (33, 1000, 130),
+          (300, 260, 4096), (64, 64, 128), (1, 512, 512), (8, 700, 1024), (32, 256, 4096), (31, 33, 258)]
+
+
+@pytest.mark.parametrize("use_ref", [False, True], ids=["tuned", "ref"])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_linear_matches_oracle(oracle, M, N, K, use_ref):
+    mode = (synth.MODE_RMS, synth.MODE_GIVEN, synth.MODE_NONE)[(M + N + K) % 3]
+    inp = synth.draw(small_case(M, N, K, mode, seed=M * 7 + N * 3 + K))
+    ref = oracle.w4a4_linear(inp.x_bits, inp.w_int, inp.s_a, inp.s_w, mode, inp.case.eps, inp.row_scale_in)
+    got = run_gpu_linear(inp, use_ref=use_ref)
+    assert np.array_equal(got["r"].view(np.uint32), ref["r"].view(np.uint32))
+    assert np.array_equal(got["q"], ref["q"])
+    assert np.array_equal(got["acc"], ref["acc"])
+    assert y_error(got["y"], ref["y"]) <= Y_TOL
+    assert np.array_equal(got["y"], ref["y"])          # same fp32 recipe on both sides: expected identical
+
+
+def test_config1_tiny(oracle):
+    for case in synth.config_cases("c1"):
+        inp = synth.draw(case)
+        ref = oracle.w4a4_linear(inp.x_bits, inp.w_int, inp.s_a, inp.s_w, case.mode, case.eps)
+        for use_ref in (False, True):
+            got = run_gpu_linear(inp, use_ref=use_ref)
+            assert np.array_equal(got["q"], ref["q"]) and np.array_equal(got["acc"], ref["acc"])
+            assert y_error(got["y"], ref["y"]) <= Y_TOL
+
+
+def test_linear_with_output_row_scale(oracle):
+    inp = synth.draw(small_case(70, 200, 384, synth.MODE_RMS, seed=21))
+    got = run_gpu_linear(inp, undo_scale=True)
+    ref = oracle.w4a4_linear(inp.x_bits, inp.w_int, inp.s_a, inp.s_w, synth.MODE_RMS, inp.case.eps, None, got["d"])
+    assert np.array_equal(got["acc"], ref["acc"])
+    assert y_error(got["y"], ref["y"]) <= Y_TOL
+
+
+def test_linear_worst_case_accumulator(oracle):
+    """All operands -8 at the largest K of the configurations: acc = 64 K exactly."""
+    M, N, K = 40, 48, 28672
+    w = np.full((N, K), -8, np.int8)
+    x = synth.f32_to_bf16_bits(np.full((M, K), -8.0, np.float32))
+    xq, _ = fptq.fptq_quantize_act(dev_bf16(x), 1.0, synth.MODE_NONE)
+    wq = fptq.fptq_pack_weights(dev(w))
+    s_w = torch.ones(N, device="cuda")
+    for fn in (fptq.fptq_w4a4_linear, fptq.fptq_w4a4_linear_ref):
+        y, acc = fn(xq, wq, M, N, K, 1.0, s_w, want_acc=True)
+        assert torch.all(acc == 64 * K)
+    w[:] = 7
+    wq = fptq.fptq_pack_weights(dev(w))
+    y, acc = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 1.0, s_w, want_acc=True)
+    assert torch.all(acc == -56 * K)
+
+
+def test_linear_is_deterministic():
+    inp = synth.draw(small_case(300, 520, 2048, synth.MODE_RMS, seed=5))
+    a = run_gpu_linear(inp)
+    b = run_gpu_linear(inp)
+    assert np.array_equal(a["acc"], b["acc"]) and np.array_equal(a["y"], b["y"])
+
+
+def test_acc_dump_is_optional(oracle):
+    inp = synth.draw(small_case(50, 260, 256, synth.MODE_NONE, seed=3))
+    a = run_gpu_linear(inp, want_acc=False)
+    b = run_gpu_linear(inp, want_acc=True)
+    assert a["acc"] is None and np.array_equal(a["y"], b["y"])
+
+
+# ------------------------------------------------------------------ error returns
+def test_error_codes():
+    x = torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fptq.FptqError) as e:
+        fptq.fptq_quantize_act(x, 0.0)
+    assert e.value.code == -6
+    with pytest.raises(fptq.FptqError) as e:
+        fptq.fptq_quantize_act(x, 1.0, 7)
+    assert e.value.code == -4
+    with pytest.raises(fptq.FptqError) as e:
+        fptq.fptq_quantize_act(x, 1.0, synth.MODE_GIVEN, 0.0, None)
+    assert e.value.code == -4
+    with pytest.raises(fptq.FptqError) as e:
+        fptq.fptq_quantize_act(x, 1.0, out=torch.zeros(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -3
+    L = fptq.lib()
+    assert L.fptq_packed_bytes(0, 128) == -2 and L.fptq_packed_bytes(4, -1) == -2
+    assert L.fptq_w4a4_linear(None, None, 1, 1, 2, 1.0, None, None, None, None, None) == -1
+    assert b"NULL" in L.fptq_last_error()
