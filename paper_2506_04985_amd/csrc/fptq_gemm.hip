@@ -9,10 +9,11 @@
 // shifts it back.  Which k lands in which byte of an operand does not matter as long as both
 // operands agree, and they do: the same code widens the same byte offsets of X and W.
 //
-// Data flow: packed tiles (rows x 64 bytes per K tile, contiguous in HBM) -> LDS by direct
-// global->LDS loads (no VGPR staging), STAGES-deep ring, one barrier per K tile -> ds_read_b128
-// fragments -> widen -> MFMA.  The 16-byte granules of a row are XOR-swizzled in LDS so that the
-// fragment reads spread over the banks.
+// Data flow: packed tiles (rows x 64 bytes per K tile, contiguous in HBM) -> LDS by buffer loads
+// that write LDS directly (no VGPR staging; rows past the end read as zero through the buffer
+// descriptor's bounds check), STAGES-deep ring, one barrier per K tile -> ds_read_b128 fragments
+// -> widen -> MFMA.  The 16-byte granules of a row are XOR-swizzled in LDS so that the fragment
+// reads are bank-conflict free.
 #include "fptq_common.h"
 
 namespace fptq {
@@ -21,13 +22,13 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-#define GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
 // s_waitcnt immediates for gfx9: vmcnt in bits [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 constexpr int WAIT_LGKM0 = 15 | (3 << 14) | (7 << 4) | (0 << 8);
 
-__device__ inline int swz(int row) { return (row >> 1) & 3; }
+// raw buffer descriptor, dword 3: 32-bit data format, no swizzle (gfx9 family encoding)
+constexpr int RSRC_FLAGS = 0x00020000;
 
 template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_>
 struct GemmCfg {
@@ -35,10 +36,13 @@ struct GemmCfg {
     static constexpr int BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32;
     static constexpr int WAVES = WAVES_N * WAVES_M, THREADS = 64 * WAVES;
     static constexpr int W_BYTES = BN * SEG, X_BYTES = BM * SEG, STAGE_BYTES = W_BYTES + X_BYTES;
-    static constexpr int W_LOADS = W_BYTES / (THREADS * 16), X_LOADS = X_BYTES / (THREADS * 16);
+    // every wave copies a contiguous run of rows of each operand tile, 1 KB (16 rows) per load
+    static constexpr int W_LOADS = W_BYTES / (WAVES * 1024), X_LOADS = X_BYTES / (WAVES * 1024);
     static constexpr int LOADS = W_LOADS + X_LOADS;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-    static_assert(W_BYTES % (THREADS * 16) == 0 && X_BYTES % (THREADS * 16) == 0, "tile must split over threads");
+    static_assert(W_BYTES % (WAVES * 1024) == 0 && X_BYTES % (WAVES * 1024) == 0, "tile must split over waves");
+    static_assert(W_LOADS <= 4 && X_LOADS <= 4, "per-load offsets must fit the 12-bit immediate");
+    static_assert(STAGES >= 3, "pipeline needs three stages");
 };
 
 // widen two packed dwords (16 nibbles) into one MFMA operand of 16 bytes, each 16 * value
@@ -52,6 +56,21 @@ __device__ inline v4i widen(int p0, int p1)
     return o;
 }
 
+// N_ consecutive 1 KB chunks with one descriptor, one VGPR offset and one LDS base: the immediate
+// offset (a compile-time constant of the instruction) advances the HBM and the LDS address together
+template <int N_, int J = 0>
+struct ChunkLoads {
+    static __device__ inline void run(__amdgpu_buffer_rsrc_t r, uint8_t *lds_base, int voff)
+    {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, LDS_PTR(lds_base), 16, voff, 0, J * 1024, 0);
+        ChunkLoads<N_, J + 1>::run(r, lds_base, voff);
+    }
+};
+template <int N_>
+struct ChunkLoads<N_, N_> {
+    static __device__ inline void run(__amdgpu_buffer_rsrc_t, uint8_t *, int) {}
+};
+
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, int tiles_m,
@@ -59,7 +78,8 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     int32_t *__restrict__ acc_out)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_n = wave % C::WAVES_N, wave_m = wave / C::WAVES_N;
 
     // ---- tile of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs; give each XCD a
@@ -78,49 +98,43 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     const int bn = band * GN + in_band % band_w, bm = in_band / band_w;
     const int n0 = bn * C::BN, m0 = bm * C::BM;
 
-    // ---- global -> LDS copy plan.  A wave-level direct load fills 1 KB of LDS: lane l lands at
-    // byte 16 l.  LDS slot s (16 bytes) of a tile holds granule (s % 4) ^ swz(row) of row s / 4.
-    int64_t w_src[C::W_LOADS], x_src[C::X_LOADS];
-#pragma unroll
-    for (int j = 0; j < C::W_LOADS; ++j) {
-        int slot = (j * C::WAVES + wave) * 64 + lane, row = slot >> 2, g = (slot & 3) ^ swz(row);
-        w_src[j] = (int64_t)min(n0 + row, N - 1) * SEG + g * 16;
-    }
-#pragma unroll
-    for (int j = 0; j < C::X_LOADS; ++j) {
-        int slot = (j * C::WAVES + wave) * 64 + lane, row = slot >> 2, g = (slot & 3) ^ swz(row);
-        x_src[j] = (int64_t)min(m0 + row, M - 1) * SEG + g * 16;
-    }
-    const int64_t w_tile_stride = (int64_t)N * SEG, x_tile_stride = (int64_t)M * SEG;
+    // ---- global -> LDS copy plan.  One K tile of an operand is rows x 64 bytes, contiguous in HBM,
+    // and its LDS image has the same linear layout except that the four 16-byte granules of a row
+    // are permuted: LDS slot s of a row holds granule s ^ swz(row), swz(row) = (row >> 2) & 3.
+    // (A ds_read_b128 is served 16 lanes at a time; the 16 rows they read then fall into 16
+    // different 16-byte bank groups: address bits 7:4 = (row % 4) * 4 + slot.)
+    // A wave-level load fills 1 KB: lane l lands at byte 16 l, i.e. row l / 4, slot l % 4, and the
+    // row's swizzle is (l / 16) & 3 for every 16-row chunk.  Each wave copies W_LOADS (X_LOADS)
+    // consecutive chunks, addressed by one VGPR offset plus 1 KB immediates, which move the HBM
+    // and the LDS address together.
+    const int lane_src = (lane >> 2) * SEG + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+    const int w_voff = (n0 + wave * (C::W_LOADS * 16)) * SEG + lane_src;
+    const int x_voff = (m0 + wave * (C::X_LOADS * 16)) * SEG + lane_src;
+    const int w_lds0 = wave * (C::W_LOADS * 1024), x_lds0 = C::W_BYTES + wave * (C::X_LOADS * 1024);
+    const int64_t w_slab = (int64_t)N * SEG, x_slab = (int64_t)M * SEG;   // bytes per K tile of all rows
 
-    auto issue_loads = [&](int kt, int stage) {
-        uint8_t *wl = lds + stage * C::STAGE_BYTES, *xl = wl + C::W_BYTES;
-        const uint8_t *wg = wq + kt * w_tile_stride, *xg = xq + kt * x_tile_stride;
-#pragma unroll
-        for (int j = 0; j < C::W_LOADS; ++j)
-            __builtin_amdgcn_global_load_lds(GLB_PTR(wg + w_src[j]), LDS_PTR(wl + (j * C::WAVES + wave) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < C::X_LOADS; ++j)
-            __builtin_amdgcn_global_load_lds(GLB_PTR(xg + x_src[j]), LDS_PTR(xl + (j * C::WAVES + wave) * 1024), 16, 0, 0);
+    // per-slab descriptors: rows past N (M) fail the bounds check and read as zero
+    auto w_desc = [&](int kt) {
+        return __builtin_amdgcn_make_buffer_rsrc((void *)(wq + kt * w_slab), 0, (int)w_slab, RSRC_FLAGS);
+    };
+    auto x_desc = [&](int kt) {
+        return __builtin_amdgcn_make_buffer_rsrc((void *)(xq + kt * x_slab), 0, (int)x_slab, RSRC_FLAGS);
+    };
+    auto issue_loads = [&](__amdgpu_buffer_rsrc_t wr, __amdgpu_buffer_rsrc_t xr, int stage) {
+        uint8_t *sb = lds + stage * C::STAGE_BYTES;
+        ChunkLoads<C::W_LOADS>::run(wr, sb + w_lds0, w_voff);
+        ChunkLoads<C::X_LOADS>::run(xr, sb + x_lds0, x_voff);
     };
 
     // ---- fragment read plan: lane (i = lane % 32, g = lane / 32) of a 32-row sub-tile reads, for
-    // K half kk, the 16-byte granule 2 kk + g of row i: its low 8 bytes feed the first MFMA of the
-    // half, the high 8 bytes the second.
+    // K half kk, granule 2 kk + g of row i (one ds_read_b128): its low 8 bytes feed the first MFMA
+    // step of the half, the high 8 bytes the second.  Sub-tile bases are multiples of 32 rows, so
+    // the swizzle depends on the lane only.
     const int fi = lane & 31, fg = lane >> 5;
-    int w_frag[C::TN], x_frag[C::TM], w_sw[C::TN], x_sw[C::TM];
+    int frag_off[2];
 #pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn) {
-        int row = (wave_n * C::TN + tn) * 32 + fi;
-        w_frag[tn] = row * SEG;
-        w_sw[tn] = swz(row);
-    }
-#pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm) {
-        int row = (wave_m * C::TM + tm) * 32 + fi;
-        x_frag[tm] = C::W_BYTES + row * SEG;
-        x_sw[tm] = swz(row);
-    }
+    for (int kk = 0; kk < 2; ++kk) frag_off[kk] = fi * SEG + (((2 * kk + fg) ^ ((fi >> 2) & 3)) << 4);
+    const int w_wave = wave_n * (C::TN * 32 * SEG), x_wave = C::W_BYTES + wave_m * (C::TM * 32 * SEG);
 
     v16i acc[C::TN][C::TM];
 #pragma unroll
@@ -130,86 +144,175 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0;
 
-    // ---- pipeline prologue: STAGES - 1 tiles in flight (tiles past the end repeat the last one,
-    // which keeps the outstanding-load count uniform)
+    // ---- software pipeline.
+    // Global side: STAGES - 1 K tiles in flight (tiles past the end repeat the last one, which keeps
+    // the outstanding-load count uniform); one barrier per K tile.
+    // Register side: a K tile is four MFMA steps of 32 values.  One ds_read_b128 per operand row
+    // brings two steps (R0: steps 0-1, R1: steps 2-3).  While the TN*TM MFMAs of step s run, the
+    // operands of step s+1 are widened (3 VALU per MFMA) and the next batch of fragment reads is
+    // issued, so neither LDS latency nor the widening sits in front of the matrix cores:
+    //   G0: MFMA step 0 | widen step 1 (R0 high)  | issue R1
+    //   G1: MFMA step 1 | widen step 2 (R1 low)
+    //   -- tile kt+1 landed, barrier, refill the buffer of tile kt-1 --
+    //   G2: MFMA step 2 | widen step 3 (R1 high)  | issue R0 of tile kt+1 | issue global loads
+    //   G3: MFMA step 3 | widen step 0' (R0' low)
+    v4i opW[2][C::TN], opX[2][C::TM], rawW[2][C::TN], rawX[2][C::TM];
+    auto read_frags = [&](int stage, int kk, v4i (&wraw)[C::TN], v4i (&xraw)[C::TM]) {
+        const uint8_t *wb = lds + stage * C::STAGE_BYTES + w_wave + frag_off[kk];
+        const uint8_t *xb = lds + stage * C::STAGE_BYTES + x_wave + frag_off[kk];
 #pragma unroll
-    for (int s = 0; s < C::STAGES - 1; ++s) issue_loads(min(s, ktiles - 1), s);
-
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const int stage = kt % C::STAGES;
-        // own loads of tile kt have landed; the barrier extends that to every wave's loads and also
-        // says everyone is done reading the buffer that is refilled next
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2)));
-        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
-        __builtin_amdgcn_s_barrier();
-        issue_loads(min(kt + C::STAGES - 1, ktiles - 1), (kt + C::STAGES - 1) % C::STAGES);
-
-        const uint8_t *base = lds + stage * C::STAGE_BYTES;
+        for (int tn = 0; tn < C::TN; ++tn) wraw[tn] = *reinterpret_cast<const v4i *>(wb + tn * (32 * SEG));
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            v4i wraw[C::TN], xraw[C::TM];
+        for (int tm = 0; tm < C::TM; ++tm) xraw[tm] = *reinterpret_cast<const v4i *>(xb + tm * (32 * SEG));
+    };
+    // MFMAs on the current operands, widening half h of the raw fragments into the next operands
+    auto group = [&](const v4i (&cw)[C::TN], const v4i (&cx)[C::TM], v4i (&nw)[C::TN], v4i (&nx)[C::TM],
+                     const v4i (&rw)[C::TN], const v4i (&rx)[C::TM], int h) {
+        constexpr int NM = C::TN * C::TM, NOP = C::TN + C::TM;
 #pragma unroll
-            for (int tn = 0; tn < C::TN; ++tn)
-                wraw[tn] = *reinterpret_cast<const v4i *>(base + w_frag[tn] + (((2 * kk + fg) ^ w_sw[tn]) << 4));
-#pragma unroll
-            for (int tm = 0; tm < C::TM; ++tm)
-                xraw[tm] = *reinterpret_cast<const v4i *>(base + x_frag[tm] + (((2 * kk + fg) ^ x_sw[tm]) << 4));
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                v4i wop[C::TN], xop[C::TM];
-#pragma unroll
-                for (int tn = 0; tn < C::TN; ++tn) wop[tn] = widen(wraw[tn][2 * h], wraw[tn][2 * h + 1]);
-#pragma unroll
-                for (int tm = 0; tm < C::TM; ++tm) xop[tm] = widen(xraw[tm][2 * h], xraw[tm][2 * h + 1]);
-#pragma unroll
-                for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-                    for (int tm = 0; tm < C::TM; ++tm)
-                        acc[tn][tm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[tn], xop[tm], acc[tn][tm], 0, 0, 0);
+        for (int i = 0; i < NM; ++i) {
+            const int tn = i / C::TM, tm = i % C::TM;
+            acc[tn][tm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cw[tn], cx[tm], acc[tn][tm], 0, 0, 0);
+            if ((i * NOP) / NM != ((i + 1) * NOP) / NM) {      // spread the NOP widenings over the NM MFMAs
+                const int o = (i * NOP) / NM;                 // order: W0, X0..X(TM-1), W1..W(TN-1)
+                if (o == 0) nw[0] = widen(rw[0][2 * h], rw[0][2 * h + 1]);
+                else if (o <= C::TM) nx[o - 1] = widen(rx[o - 1][2 * h], rx[o - 1][2 * h + 1]);
+                else nw[o - C::TM] = widen(rw[o - C::TM][2 * h], rw[o - C::TM][2 * h + 1]);
             }
         }
-    }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the repeated tail loads before the LDS dies
+    };
+    // pin the interleave: one MFMA, then its share of VALU work, optionally one LDS read / one
+    // global->LDS load
+    auto pin = [&](int n_ds, int n_vmem) {
+        constexpr int NM = C::TN * C::TM;
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i >= NM - n_vmem) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-    // ---- epilogue.  W was the A operand, so the accumulator tile is [n][m]: a lane owns token
-    // m = lane % 32 and, per register quad, four consecutive output channels
-    // n = 8 * (r / 4) + 4 * (lane / 32) + (r % 4).
-    const bool vec_ok = (N % 4) == 0;
+#pragma unroll
+    for (int s = 0; s < C::STAGES - 1; ++s) issue_loads(w_desc(min(s, ktiles - 1)), x_desc(min(s, ktiles - 1)), s);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2)));
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, 0, rawW[0], rawX[0]);
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn) opW[0][tn] = widen(rawW[0][tn][0], rawW[0][tn][1]);
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm) opX[0][tm] = widen(rawX[0][tm][0], rawX[0][tm][1]);
+    __builtin_amdgcn_sched_barrier(0);
+
+    int stage = 0;      // ring position of tile kt
+    // descriptors of the tile fetched during iteration kt; rebuilt one iteration ahead, inside G3,
+    // so that the scalar work does not sit between the barrier and the first MFMAs of G2
+    __amdgpu_buffer_rsrc_t wr = w_desc(min(C::STAGES - 1, ktiles - 1)), xr = x_desc(min(C::STAGES - 1, ktiles - 1));
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const int stage_next = stage + 1 == C::STAGES ? 0 : stage + 1;
+        const int stage_fill = stage == 0 ? C::STAGES - 1 : stage - 1;   // = (kt + STAGES - 1) % STAGES
+        // G0
+        read_frags(stage, 1, rawW[1], rawX[1]);
+        group(opW[0], opX[0], opW[1], opX[1], rawW[0], rawX[0], 1);
+        pin(C::TN + C::TM, 0);
+        // G1
+        group(opW[1], opX[1], opW[0], opX[0], rawW[1], rawX[1], 0);
+        pin(0, 0);
+        // own loads of tile kt + 1 have landed; the barrier extends that to every wave's loads and
+        // also says everyone is done reading tile kt - 1, whose buffer is refilled next
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 3)));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        // G2 (after the last tile the fragment reads hit a repeated copy; its results are unused)
+        read_frags(stage_next, 0, rawW[0], rawX[0]);
+        issue_loads(wr, xr, stage_fill);
+        group(opW[0], opX[0], opW[1], opX[1], rawW[1], rawX[1], 1);
+        pin(C::TN + C::TM, C::LOADS);
+        // G3
+        wr = w_desc(min(kt + C::STAGES, ktiles - 1));
+        xr = x_desc(min(kt + C::STAGES, ktiles - 1));
+        group(opW[1], opX[1], opW[0], opX[0], rawW[0], rawX[0], 0);
+        pin(0, 0);
+        stage = stage_next;
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the repeated tail loads before LDS is reused
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+    __builtin_amdgcn_s_barrier();
+
+    // ---- epilogue.  W was the A operand, so an accumulator tile is [n][m]: a lane owns token
+    // m = lane % 32 and, per register quad q, four consecutive output channels
+    // n = 8 q + 4 (lane / 32) + (r % 4).  acc >> 8 is exact (the register holds 256 * acc).
+    // The bf16 results go through a wave-private LDS patch ([32 tokens][TN * 32 channels], padded
+    // rows) so that HBM sees whole 16-byte-per-lane row segments instead of scattered quads.
+    constexpr int WN = C::TN * 32;                    // channels per wave
+    constexpr int PATCH_STRIDE = WN * 2 + 16;         // bytes per token row in the patch
+    uint8_t *patch = lds + wave * (32 * PATCH_STRIDE);
+    const int nw0 = n0 + wave_n * WN;
+    float cw[C::TN][4][4];
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int n = nw0 + tn * 32 + 8 * q + 4 * fg + e;
+                cw[tn][q][e] = s_a * s_w[min(n, N - 1)];
+            }
+    const bool vec_ok = (N % 8) == 0;
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm) {
-        const int m = m0 + (wave_m * C::TM + tm) * 32 + fi;
-        if (m >= M) continue;
-        const float dm = d ? d[m] : 1.0f;
+        const int mw0 = m0 + (wave_m * C::TM + tm) * 32;
+        const int m = mw0 + fi;
+        const float dm = (d && m < M) ? d[m] : 1.0f;
 #pragma unroll
-        for (int tn = 0; tn < C::TN; ++tn) {
+        for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = n0 + (wave_n * C::TN + tn) * 32 + 8 * q + 4 * fg;
-                if (n >= N) continue;
                 uint16_t o[4];
-                int32_t a[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    a[e] = acc[tn][tm][4 * q + e] >> 8;      // exact: the register holds 256 * acc
-                    if (n + e < N) {
-                        float yf = (float)a[e] * (s_a * s_w[n + e]);
-                        if (d) yf = yf * dm;
-                        o[e] = bf16_rne(yf);
-                    }
+                    float yf = (float)(acc[tn][tm][4 * q + e] >> 8) * cw[tn][q][e];
+                    if (d) yf = yf * dm;
+                    o[e] = bf16_rne(yf);
                 }
-                const int64_t off = (int64_t)m * N + n;
-                if (vec_ok) {   // N % 4 == 0 and n % 4 == 0: the quad is whole and 8-byte aligned
-                    *reinterpret_cast<uint2 *>(y + off) = make_uint2(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16));
-                    if (acc_out) *reinterpret_cast<int4 *>(acc_out + off) = make_int4(a[0], a[1], a[2], a[3]);
-                } else {
+                *reinterpret_cast<uint2 *>(patch + fi * PATCH_STRIDE + (tn * 32 + 8 * q + 4 * fg) * 2) =
+                    make_uint2(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16));
+            }
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+        __builtin_amdgcn_wave_barrier();
+        // read back row segments: 16 bytes (8 channels) per lane, WN / 8 lanes per token row
+        constexpr int LANES_PER_ROW = WN / 8, ROWS_PER_PASS = 64 / LANES_PER_ROW;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < N) {
-                            y[off + e] = o[e];
-                            if (acc_out) acc_out[off + e] = a[e];
-                        }
+        for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
+            const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW, col = (lane % LANES_PER_ROW) * 8;
+            const uint4 v = *reinterpret_cast<const uint4 *>(patch + row * PATCH_STRIDE + col * 2);
+            const int mm = mw0 + row, nn = nw0 + col;
+            if (mm < M && nn < N) {
+                uint16_t *dst = y + (int64_t)mm * N + nn;
+                if (vec_ok) {
+                    *reinterpret_cast<uint4 *>(dst) = v;
+                } else {
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (nn + e < N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
                 }
             }
+        }
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+        __builtin_amdgcn_wave_barrier();
+        if (acc_out) {      // parity dump of the integer accumulators (not a timed path)
+#pragma unroll
+            for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int n = nw0 + tn * 32 + 8 * q + 4 * fg + e;
+                        if (m < M && n < N) acc_out[(int64_t)m * N + n] = acc[tn][tm][4 * q + e] >> 8;
+                    }
         }
     }
 }
@@ -235,9 +338,10 @@ static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, in
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                               const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
 {
-    // the widened accumulator is 256 * acc and |acc| <= 64 K: beyond this K it could leave int32
-    if (K > 131071 || M > 0x7fffffff || N > 0x7fffffff || M * N > ((int64_t)1 << 40))
-        return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    // Limits of this kernel: the widened accumulator is 256 * acc with |acc| <= 64 K, and one K tile
+    // of all rows (rows * 64 bytes) must fit a 32-bit buffer descriptor.  Beyond them the simple
+    // kernel answers.
+    if (K > 131071 || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
     typedef GemmCfg<2, 2, 4, 4, 4> Big;     // 256 x 256 tile, 4 waves of 128 x 128, 128 KB LDS
     return launch_cfg<Big>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
 }
