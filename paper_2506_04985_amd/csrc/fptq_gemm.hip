@@ -41,7 +41,7 @@ struct GemmCfg {
     static constexpr int LOADS = W_LOADS + X_LOADS;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
     static_assert(W_BYTES % (WAVES * 1024) == 0 && X_BYTES % (WAVES * 1024) == 0, "tile must split over waves");
-    static_assert(W_LOADS <= 4 && X_LOADS <= 4, "per-load offsets must fit the 12-bit immediate");
+    static_assert(W_LOADS == 4 && X_LOADS == 4, "the fill schedule below issues one W and one X chunk per quarter");
     static_assert(STAGES >= 3, "pipeline needs three stages");
 };
 
@@ -56,22 +56,26 @@ __device__ inline v4i widen(int p0, int p1)
     return o;
 }
 
-// N_ consecutive 1 KB chunks with one descriptor, one VGPR offset and one LDS base: the immediate
-// offset (a compile-time constant of the instruction) advances the HBM and the LDS address together
-template <int N_, int J = 0>
-struct ChunkLoads {
-    static __device__ inline void run(__amdgpu_buffer_rsrc_t r, uint8_t *lds_base, int voff)
-    {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, LDS_PTR(lds_base), 16, voff, 0, J * 1024, 0);
-        ChunkLoads<N_, J + 1>::run(r, lds_base, voff);
-    }
-};
-template <int N_>
-struct ChunkLoads<N_, N_> {
-    static __device__ inline void run(__amdgpu_buffer_rsrc_t, uint8_t *, int) {}
-};
+// two fp32 -> packed bf16 pair (round to nearest even, hardware conversion)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack_bf16(float lo, float hi)
+{
+    float2_t f = {lo, hi};
+    bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, b);
+}
 
-template <class C>
+// One 1 KB chunk (16 rows) of an operand tile, HBM -> LDS.  J is the chunk number inside the run of
+// chunks this wave copies: the immediate offset (a compile-time constant of the instruction)
+// advances the HBM and the LDS address together, so all chunks share one VGPR offset and one LDS base.
+template <int J>
+__device__ inline void load_chunk(__amdgpu_buffer_rsrc_t r, uint8_t *lds_base, int voff)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, LDS_PTR(lds_base), 16, voff, 0, J * 1024, 0);
+}
+
+template <class C, bool ALIGNED, bool DUMP>
 __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, int tiles_m,
     int tiles_n, float s_a, const float *__restrict__ s_w, const float *__restrict__ d, uint16_t *__restrict__ y,
@@ -120,10 +124,13 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     auto x_desc = [&](int kt) {
         return __builtin_amdgcn_make_buffer_rsrc((void *)(xq + kt * x_slab), 0, (int)x_slab, RSRC_FLAGS);
     };
-    auto issue_loads = [&](__amdgpu_buffer_rsrc_t wr, __amdgpu_buffer_rsrc_t xr, int stage) {
+    // quarter q (0..3) of the fill of one K tile: one W chunk and one X chunk
+    auto fill_quarter = [&](__amdgpu_buffer_rsrc_t wr, __amdgpu_buffer_rsrc_t xr, int stage, int q) {
         uint8_t *sb = lds + stage * C::STAGE_BYTES;
-        ChunkLoads<C::W_LOADS>::run(wr, sb + w_lds0, w_voff);
-        ChunkLoads<C::X_LOADS>::run(xr, sb + x_lds0, x_voff);
+        if (q == 0) { load_chunk<0>(wr, sb + w_lds0, w_voff); load_chunk<0>(xr, sb + x_lds0, x_voff); }
+        if (q == 1) { load_chunk<1>(wr, sb + w_lds0, w_voff); load_chunk<1>(xr, sb + x_lds0, x_voff); }
+        if (q == 2) { load_chunk<2>(wr, sb + w_lds0, w_voff); load_chunk<2>(xr, sb + x_lds0, x_voff); }
+        if (q == 3) { load_chunk<3>(wr, sb + w_lds0, w_voff); load_chunk<3>(xr, sb + x_lds0, x_voff); }
     };
 
     // ---- fragment read plan: lane (i = lane % 32, g = lane / 32) of a 32-row sub-tile reads, for
@@ -145,17 +152,18 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
             for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0;
 
     // ---- software pipeline.
-    // Global side: STAGES - 1 K tiles in flight (tiles past the end repeat the last one, which keeps
-    // the outstanding-load count uniform); one barrier per K tile.
-    // Register side: a K tile is four MFMA steps of 32 values.  One ds_read_b128 per operand row
-    // brings two steps (R0: steps 0-1, R1: steps 2-3).  While the TN*TM MFMAs of step s run, the
-    // operands of step s+1 are widened (3 VALU per MFMA) and the next batch of fragment reads is
-    // issued, so neither LDS latency nor the widening sits in front of the matrix cores:
-    //   G0: MFMA step 0 | widen step 1 (R0 high)  | issue R1
-    //   G1: MFMA step 1 | widen step 2 (R1 low)
-    //   -- tile kt+1 landed, barrier, refill the buffer of tile kt-1 --
-    //   G2: MFMA step 2 | widen step 3 (R1 high)  | issue R0 of tile kt+1 | issue global loads
-    //   G3: MFMA step 3 | widen step 0' (R0' low)
+    // A K tile is four MFMA steps of 32 values, i.e. four groups G0..G3 of TN*TM MFMAs.  One
+    // ds_read_b128 per operand row brings two steps (R0: steps 0-1, R1: steps 2-3).  While the
+    // MFMAs of step s run, the operands of step s+1 are widened (3 VALU per MFMA), the next batch of
+    // fragment reads is issued one read every other MFMA, and the HBM->LDS fill of a later tile is
+    // issued a quarter per group.  Spreading the LDS reads and the fill matters: the four waves run
+    // in lock step, and a burst of either backs up the LDS / address queues and stalls MFMA issue.
+    //   G0(kt): MFMA step 0 | widen step 1 (R0 high)  | read R1(kt)     | fill(kt+S-1) quarter 2
+    //   G1(kt): MFMA step 1 | widen step 2 (R1 low)   |                 | fill(kt+S-1) quarter 3
+    //   -- tile kt+1 has landed; barrier; every wave is done reading tile kt --
+    //   G2(kt): MFMA step 2 | widen step 3 (R1 high)  | read R0(kt+1)   | fill(kt+S) quarter 0, into tile kt's buffer
+    //   G3(kt): MFMA step 3 | widen step 0' (R0' low) |                 | fill(kt+S) quarter 1
+    // Tiles past the end repeat the last one, which keeps the outstanding-load count uniform.
     v4i opW[2][C::TN], opX[2][C::TM], rawW[2][C::TN], rawX[2][C::TM];
     auto read_frags = [&](int stage, int kk, v4i (&wraw)[C::TN], v4i (&xraw)[C::TM]) {
         const uint8_t *wb = lds + stage * C::STAGE_BYTES + w_wave + frag_off[kk];
@@ -181,23 +189,34 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
             }
         }
     };
-    // pin the interleave: one MFMA, then its share of VALU work, optionally one LDS read / one
-    // global->LDS load
-    auto pin = [&](int n_ds, int n_vmem) {
+    // pin the interleave of one group: one MFMA, then its share of VALU work; an LDS read after
+    // every other MFMA when the group issues reads; the two fill loads in the middle
+    auto pin = [&](bool reads) {
         constexpr int NM = C::TN * C::TM;
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (i >= NM - n_vmem) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            if (reads && (i * (C::TN + C::TM)) / NM != ((i + 1) * (C::TN + C::TM)) / NM)
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i == NM / 4 || i == (3 * NM) / 4) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    auto clampk = [&](int kt) { return min(kt, ktiles - 1); };
 #pragma unroll
-    for (int s = 0; s < C::STAGES - 1; ++s) issue_loads(w_desc(min(s, ktiles - 1)), x_desc(min(s, ktiles - 1)), s);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2)));
+    for (int s = 0; s < C::STAGES - 1; ++s) {
+        __amdgpu_buffer_rsrc_t wr = w_desc(clampk(s)), xr = x_desc(clampk(s));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) fill_quarter(wr, xr, s, q);
+    }
+    // descriptors of the fill that is half way (tile kt+S-1) and of the one that starts in G2 (tile kt+S)
+    __amdgpu_buffer_rsrc_t wr_a = w_desc(clampk(C::STAGES - 1)), xr_a = x_desc(clampk(C::STAGES - 1));
+    __amdgpu_buffer_rsrc_t wr_b = w_desc(clampk(C::STAGES)), xr_b = x_desc(clampk(C::STAGES));
+    fill_quarter(wr_a, xr_a, C::STAGES - 1, 0);
+    fill_quarter(wr_a, xr_a, C::STAGES - 1, 1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2) + C::LOADS / 2));   // tile 0 is in
     __builtin_amdgcn_s_barrier();
     read_frags(0, 0, rawW[0], rawX[0]);
 #pragma unroll
@@ -207,34 +226,36 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     __builtin_amdgcn_sched_barrier(0);
 
     int stage = 0;      // ring position of tile kt
-    // descriptors of the tile fetched during iteration kt; rebuilt one iteration ahead, inside G3,
-    // so that the scalar work does not sit between the barrier and the first MFMAs of G2
-    __amdgpu_buffer_rsrc_t wr = w_desc(min(C::STAGES - 1, ktiles - 1)), xr = x_desc(min(C::STAGES - 1, ktiles - 1));
     for (int kt = 0; kt < ktiles; ++kt) {
         const int stage_next = stage + 1 == C::STAGES ? 0 : stage + 1;
-        const int stage_fill = stage == 0 ? C::STAGES - 1 : stage - 1;   // = (kt + STAGES - 1) % STAGES
+        const int stage_prev = stage == 0 ? C::STAGES - 1 : stage - 1;   // holds tile kt+S-1 (being filled)
         // G0
         read_frags(stage, 1, rawW[1], rawX[1]);
+        fill_quarter(wr_a, xr_a, stage_prev, 2);
         group(opW[0], opX[0], opW[1], opX[1], rawW[0], rawX[0], 1);
-        pin(C::TN + C::TM, 0);
+        pin(true);
         // G1
+        fill_quarter(wr_a, xr_a, stage_prev, 3);
         group(opW[1], opX[1], opW[0], opX[0], rawW[1], rawX[1], 0);
-        pin(0, 0);
-        // own loads of tile kt + 1 have landed; the barrier extends that to every wave's loads and
-        // also says everyone is done reading tile kt - 1, whose buffer is refilled next
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 3)));
+        pin(false);
+        // own loads of tile kt+1 have landed (younger: all of tiles kt+2 .. kt+S-1); the barrier
+        // extends that to every wave's loads and says every wave is done reading tile kt
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2)));
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         // G2 (after the last tile the fragment reads hit a repeated copy; its results are unused)
         read_frags(stage_next, 0, rawW[0], rawX[0]);
-        issue_loads(wr, xr, stage_fill);
+        fill_quarter(wr_b, xr_b, stage, 0);
         group(opW[0], opX[0], opW[1], opX[1], rawW[1], rawX[1], 1);
-        pin(C::TN + C::TM, C::LOADS);
+        pin(true);
         // G3
-        wr = w_desc(min(kt + C::STAGES, ktiles - 1));
-        xr = x_desc(min(kt + C::STAGES, ktiles - 1));
+        fill_quarter(wr_b, xr_b, stage, 1);
+        wr_a = wr_b;
+        xr_a = xr_b;
+        wr_b = w_desc(clampk(kt + C::STAGES + 1));
+        xr_b = x_desc(clampk(kt + C::STAGES + 1));
         group(opW[1], opX[1], opW[0], opX[0], rawW[0], rawX[0], 0);
-        pin(0, 0);
+        pin(false);
         stage = stage_next;
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the repeated tail loads before LDS is reused
@@ -243,24 +264,21 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
 
     // ---- epilogue.  W was the A operand, so an accumulator tile is [n][m]: a lane owns token
     // m = lane % 32 and, per register quad q, four consecutive output channels
-    // n = 8 q + 4 (lane / 32) + (r % 4).  acc >> 8 is exact (the register holds 256 * acc).
-    // The bf16 results go through a wave-private LDS patch ([32 tokens][TN * 32 channels], padded
-    // rows) so that HBM sees whole 16-byte-per-lane row segments instead of scattered quads.
+    // n = 8 q + 4 (lane / 32) + (r % 4).  The register holds 256 * acc; (float)(256 * acc) equals
+    // 256 * (float)acc exactly (acc has fewer than 24 significant bits), and the 2^-8 is folded into
+    // the channel scale, which is exact as well, so y = bf16((float)acc * (s_a * s_w[n]) [* d_t]) to
+    // the bit.  The bf16 results go through a wave-private LDS patch ([32 tokens][TN * 32 channels],
+    // padded rows) so that HBM sees whole 16-byte-per-lane row segments instead of scattered quads.
     constexpr int WN = C::TN * 32;                    // channels per wave
     constexpr int PATCH_STRIDE = WN * 2 + 16;         // bytes per token row in the patch
-    uint8_t *patch = lds + wave * (32 * PATCH_STRIDE);
+    constexpr int WAVE_LDS = 32 * PATCH_STRIDE + WN * 4;
+    uint8_t *patch = lds + wave * WAVE_LDS;
+    float *cwbuf = reinterpret_cast<float *>(patch + 32 * PATCH_STRIDE);
     const int nw0 = n0 + wave_n * WN;
-    float cw[C::TN][4][4];
 #pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                int n = nw0 + tn * 32 + 8 * q + 4 * fg + e;
-                cw[tn][q][e] = s_a * s_w[min(n, N - 1)];
-            }
-    const bool vec_ok = (N % 8) == 0;
+    for (int c = lane; c < WN; c += 64) cwbuf[c] = (s_a * s_w[min(nw0 + c, N - 1)]) * 0.00390625f;
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm) {
         const int mw0 = m0 + (wave_m * C::TM + tm) * 32;
@@ -270,15 +288,15 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                uint16_t o[4];
+                const float4 c4 = *reinterpret_cast<const float4 *>(cwbuf + tn * 32 + 8 * q + 4 * fg);
+                float yf[4] = {(float)acc[tn][tm][4 * q + 0] * c4.x, (float)acc[tn][tm][4 * q + 1] * c4.y,
+                               (float)acc[tn][tm][4 * q + 2] * c4.z, (float)acc[tn][tm][4 * q + 3] * c4.w};
+                if (d) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float yf = (float)(acc[tn][tm][4 * q + e] >> 8) * cw[tn][q][e];
-                    if (d) yf = yf * dm;
-                    o[e] = bf16_rne(yf);
+                    for (int e = 0; e < 4; ++e) yf[e] = yf[e] * dm;
                 }
                 *reinterpret_cast<uint2 *>(patch + fi * PATCH_STRIDE + (tn * 32 + 8 * q + 4 * fg) * 2) =
-                    make_uint2(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16));
+                    make_uint2(pack_bf16(yf[0], yf[1]), pack_bf16(yf[2], yf[3]));
             }
         __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_wave_barrier();
@@ -291,7 +309,7 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
             const int mm = mw0 + row, nn = nw0 + col;
             if (mm < M && nn < N) {
                 uint16_t *dst = y + (int64_t)mm * N + nn;
-                if (vec_ok) {
+                if (ALIGNED) {       // N % 8 == 0: the segment is whole and 16-byte aligned
                     *reinterpret_cast<uint4 *>(dst) = v;
                 } else {
                     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -303,7 +321,7 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         }
         __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_wave_barrier();
-        if (acc_out) {      // parity dump of the integer accumulators (not a timed path)
+        if (DUMP) {      // parity dump of the integer accumulators (never a timed path)
 #pragma unroll
             for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
@@ -317,12 +335,12 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     }
 }
 
-template <class C>
-static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                             const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+template <class C, bool ALIGNED, bool DUMP>
+static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                              const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
 {
     static bool attr_set = false;
-    auto kern = linear_mfma_kernel<C>;
+    auto kern = linear_mfma_kernel<C, ALIGNED, DUMP>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
@@ -333,6 +351,17 @@ static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, in
     kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(C::THREADS), C::LDS_BYTES, s>>>(
         xq, wq, (int)M, (int)N, (int)k_tiles(K), (int)tiles_m, (int)tiles_n, s_a, s_w, d, y, acc);
     return hipGetLastError();
+}
+
+template <class C>
+static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                             const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+{
+    const bool aligned = N % 8 == 0;
+    if (acc) return aligned ? launch_inst<C, true, true>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s)
+                            : launch_inst<C, false, true>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    return aligned ? launch_inst<C, true, false>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s)
+                   : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
 }
 
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
