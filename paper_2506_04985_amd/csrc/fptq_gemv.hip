@@ -1,12 +1,124 @@
-// Few-token (decode) kernel of the quantized linear layer.
+// Few-token (decode) kernel of the quantized linear layer: M <= 32 tokens against packed INT4
+// weights, INT32 accumulation, float-scale epilogue to bf16 (App. J and App. B of the paper).
+//
+// The job is bound by reading the packed weights once from HBM, so the kernel is built around
+// keeping many weight loads in flight per CU and doing as little else as possible:
+//   - a workgroup owns 16 output channels; its WAVES waves split K (wave w takes K tiles
+//     w, w + WAVES, ...), so even the smallest matrices give every CU a workgroup, and several
+//     workgroups fit a CU (no LDS ring, few registers), which overlaps their ramp-up and tails;
+//   - weights go HBM -> registers directly in MFMA operand order: lane (i = l % 16, g = l / 16)
+//     loads granule g (16 bytes, 32 values) of row i, so a wave-level load covers one contiguous
+//     1 KB chunk (16 rows x 64 bytes) and U such loads are in flight per wave;
+//   - the activations of the same K tile (M x 64 bytes, L2 resident) are loaded the same way,
+//     token rows clamped to M - 1 (duplicate columns are computed and dropped);
+//   - v_mfma_i32_16x16x64_i8 does the arithmetic: A = 16 weight rows, B = 16 tokens (two B
+//     operands when M > 16).  Nibbles are widened to bytes exactly as in the prefill kernel
+//     (16 * value on both sides, accumulator = 256 * acc, shifted back in the epilogue);
+//   - the WAVES partial accumulators are summed through LDS (integers: exact, order-free).
 #include "fptq_common.h"
 
 namespace fptq {
 
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ inline v4i dec_widen(int p0, int p1)
+{
+    v4i o;
+    o.x = (p0 << 4) & (int)0xF0F0F0F0;
+    o.y = p0 & (int)0xF0F0F0F0;
+    o.z = (p1 << 4) & (int)0xF0F0F0F0;
+    o.w = p1 & (int)0xF0F0F0F0;
+    return o;
+}
+
+// MT = number of 16-token groups (1: M <= 16, 2: M <= 32); U = K tiles in flight per wave
+template <int WAVES, int U, int MT>
+__global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
+    const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, float s_a,
+    const float *__restrict__ s_w, const float *__restrict__ d, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
+{
+    __shared__ int32_t red[WAVES * MT * 256];          // [WAVES][MT][16 tokens][16 channels]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n0 = blockIdx.x * 16;
+    const int fi = lane & 15, fg = lane >> 4;
+
+    // lane (i, g): granule g of weight row n0 + i, and of token row i (clamped: rows past the end
+    // repeat the last one; what they produce is never stored).  The low 8 bytes of a granule feed
+    // the first MFMA of the K tile (k = 32 g + 0..15), the high 8 bytes the second.
+    const int64_t w_slab = (int64_t)N * SEG, x_slab = (int64_t)M * SEG;
+    const uint8_t *wp = wq + (int64_t)min(n0 + fi, N - 1) * SEG + fg * 16;
+    const uint8_t *xp[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xp[mt] = xq + (int64_t)min(mt * 16 + fi, M - 1) * SEG + fg * 16;
+
+    const int T = wave < ktiles ? (ktiles - wave + WAVES - 1) / WAVES : 0;   // K tiles of this wave
+    v4i acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = v4i{0, 0, 0, 0};
+
+    for (int base = 0; base < T; base += U) {
+        v4i wv[U], xv[MT][U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u < T) wv[u] = *reinterpret_cast<const v4i *>(wp + (int64_t)(wave + (base + u) * WAVES) * w_slab);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u < T) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    xv[mt][u] = *reinterpret_cast<const v4i *>(xp[mt] + (int64_t)(wave + (base + u) * WAVES) * x_slab);
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u < T) {
+                const v4i w0 = dec_widen(wv[u][0], wv[u][1]), w1 = dec_widen(wv[u][2], wv[u][3]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const v4i x0 = dec_widen(xv[mt][u][0], xv[mt][u][1]), x1 = dec_widen(xv[mt][u][2], xv[mt][u][3]);
+                    acc[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, x0, acc[mt], 0, 0, 0);
+                    acc[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1, x1, acc[mt], 0, 0, 0);
+                }
+            }
+    }
+
+    // ---- reduce the WAVES partial tiles through LDS.  D layout of the 16x16 MFMA: lane l, register
+    // r holds D[row = 4 (l / 16) + r][col = l % 16]; rows are output channels, columns tokens.
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[((wave * MT + mt) * 16 + fi) * 16 + 4 * fg + r] = acc[mt][r];
+    __syncthreads();
+    for (int o = tid; o < MT * 256; o += 64 * WAVES) {
+        const int mt = o >> 8, j = (o >> 4) & 15, i = o & 15;     // token group, token, channel
+        int32_t sum = 0;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[((w * MT + mt) * 16 + j) * 16 + i];
+        const int t = mt * 16 + j, n = n0 + i;
+        if (t < M && n < N) {
+            const int32_t a = sum >> 8;                // exact: the sum is 256 * acc
+            y[(int64_t)t * N + n] = dequant_bf16(a, s_a * s_w[n], d, t);
+            if (acc_out) acc_out[(int64_t)t * N + n] = a;
+        }
+    }
+}
+
+template <int WAVES, int U, int MT>
+static hipError_t launch_decode_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                                    const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+{
+    linear_decode_kernel<WAVES, U, MT><<<dim3((unsigned)((N + 15) / 16)), dim3(64 * WAVES), 0, s>>>(
+        xq, wq, (int)M, (int)N, (int)k_tiles(K), s_a, s_w, d, y, acc);
+    return hipGetLastError();
+}
+
 hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                                 const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
 {
-    return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    // Limits: M <= 32; 256 * acc must stay in int32; the grid is one workgroup per 16 channels.
+    if (M > 32 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (M <= 16) return launch_decode_cfg<8, 8, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    return launch_decode_cfg<8, 8, 2>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
 }
 
 }  // namespace fptq
