@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A4 static-quantized linear path on one MI355X.
+
+A step is one pass of the whole hot path over the Llama-2-7B-shaped MLP of the second benchmark
+configuration (2048 tokens): quantize X (per-token RMS scale) -> gate GEMM -> up GEMM ->
+quantize the down-projection input (given per-token scale) -> down GEMM.  Inputs are synthetic,
+seeded, and resident in HBM before the timed region.  One JSON line is printed:
+
+  value      whole-step throughput in TOP/s (2*M*N*K of the three GEMMs / step time, quantize
+             kernels included in the time)
+  roofline   the MFMA GEMM kernel: algorithmic ops per launch / average launch duration (HIP
+             events on the launch stream) against the 5.0 POP/s dense INT8 MFMA peak
+  cpu_baseline  the CPU oracle (never tuned) on the same workload, timed on the host cores
+  decode     few-token (M = 1, 8, 32) GB/s over the Llama-3-8B layer matrices, graph-replayed and
+             cycled over > 256 MB of distinct weight copies so nothing is served from cache
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA, TOP/s
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, GB/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode summary")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2506_04985_amd import binding as fptq
+    from paper_2506_04985_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    fptq.lib()          # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    # ------------------------------------------------------------------ workload: config c2
+    gate, up, down = synth.config_cases("c2")
+    in_gu = synth.draw(gate, with_weights=False)             # X shared by gate and up
+    in_dn = synth.draw(down, with_weights=False)
+    M = gate.M
+    x_gu, x_dn = dev_bf16(in_gu.x_bits), dev_bf16(in_dn.x_bits)
+    r_dn = torch.from_numpy(in_dn.row_scale_in).to(dev)
+    layers = []
+    for case in (gate, up, down):
+        w, s_w = synth.draw_weights(case)
+        layers.append((case, fptq.fptq_pack_weights(torch.from_numpy(w).to(dev)), torch.from_numpy(s_w).to(dev)))
+        del w
+    xq_gu = torch.empty(fptq.fptq_packed_bytes(M, gate.K), dtype=torch.uint8, device=dev)
+    xq_dn = torch.empty(fptq.fptq_packed_bytes(M, down.K), dtype=torch.uint8, device=dev)
+    r_out = torch.empty(M, dtype=torch.float32, device=dev)
+    ys = [torch.empty((M, c.N), dtype=torch.bfloat16, device=dev) for c, _, _ in layers]
+    s_gu, s_dn = float(in_gu.s_a), float(in_dn.s_a)
+    gemm_events = []
+
+    def step(record=False):
+        fptq.fptq_quantize_act(x_gu, s_gu, gate.mode, gate.eps, None, out=xq_gu, row_scale_out=r_out)
+        for i, (case, wq, s_w) in enumerate(layers):
+            if i == 2:
+                fptq.fptq_quantize_act(x_dn, s_dn, down.mode, down.eps, r_dn, out=xq_dn, row_scale_out=r_out)
+            xq, s_a = (xq_gu, s_gu) if i < 2 else (xq_dn, s_dn)
+            if record:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            fptq.fptq_w4a4_linear(xq, wq, M, case.N, case.K, s_a, s_w, out=ys[i])
+            if record:
+                e1.record()
+                gemm_events.append((case, e0, e1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(record=True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    ops_step = sum(c.ops for c, _, _ in layers)
+    value = ops_step / (ms_per_step * 1e-3) / 1e12
+
+    gemm_ms = [e0.elapsed_time(e1) for _, e0, e1 in gemm_events]
+    gemm_ops = [c.ops for c, _, _ in gemm_events]
+    avg_ms = float(np.mean(gemm_ms))
+    achieved = float(np.mean(gemm_ops)) / (avg_ms * 1e-3) / 1e12
+    roofline = {"kernel": "linear_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 1),
+                "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
+                "avg_launch_us": round(avg_ms * 1e3, 2), "ops_per_launch": int(np.mean(gemm_ops)), "traffic": None}
+
+    # the same three GEMMs on uniform random INT4 activations (dense operands draw more power)
+    dense = {}
+    for name, rows, K in (("gate_up_input", M, gate.K), ("down_input", M, down.K)):
+        dense[name] = torch.randint(0, 256, (fptq.fptq_packed_bytes(rows, K),), dtype=torch.uint8, device=dev)
+    def dense_pass():
+        for i, (case, wq, s_w) in enumerate(layers):
+            fptq.fptq_w4a4_linear(dense["gate_up_input" if i < 2 else "down_input"], wq, M, case.N, case.K, 1.0, s_w, out=ys[i])
+    for _ in range(3):
+        dense_pass()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        dense_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    dense_tops = ops_step / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12
+
+    out = {"metric": "W4A4 linear TOPS (prefill)", "value": round(value, 1), "unit": "TOP/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 MFMA on int4 operands, int32 accumulate",
+           "data": "synthetic",
+           "config": {"workload": "c2: Llama-2-7B-shaped MLP, prefill 2048 tokens: quantize X, gate and up [11008x4096], "
+                                  "quantize X_down, down [4096x11008]", "tokens": M, "ops_per_step": ops_step},
+           "pct_int8_mfma_peak": round(value / INT8_MFMA_PEAK_TOPS * 100, 2),
+           "gemm_only_dense_int4_activations_tops": round(dense_tops, 1),
+           "roofline": roofline}
+
+    # ------------------------------------------------------------------ decode summary (config c4)
+    if not args.no_decode:
+        out["decode"] = decode_summary(torch, fptq, dev)
+
+    # ------------------------------------------------------------------ CPU oracle beside it
+    if not args.no_cpu:
+        from oracle import linear as oracle
+        oracle.lib()
+        cpu_s = 0.0
+        for case, inp in ((gate, in_gu), (up, in_gu), (down, in_dn)):
+            w, s_w = synth.draw_weights(case)
+            t1 = time.perf_counter()
+            oracle.w4a4_linear_timed(inp.x_bits, w, inp.s_a, s_w, case.mode, case.eps, inp.row_scale_in)
+            cpu_s += time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": round(ops_step / cpu_s / 1e12, 4), "unit": "TOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "seconds": round(cpu_s, 2),
+                               "sample": "the full c2 step once (2048 tokens, three linears, quantizer included; weight "
+                                         "generation excluded)"}
+    print(json.dumps(out))
+
+
+def decode_summary(torch, fptq, dev):
+    """GB/s of fptq_w4a4_linear at M = 1, 8, 32 over the four Llama-3-8B layer matrices."""
+    layers = {"qkv": (6144, 4096), "o": (4096, 4096), "gate_up": (28672, 4096), "down": (4096, 14336)}
+    res = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    weights = {}
+    for name, (N, K) in layers.items():
+        wbytes = fptq.fptq_packed_bytes(N, K)
+        copies = max(2, (320 << 20) // wbytes + 1)
+        weights[name] = [torch.randint(0, 256, (wbytes,), dtype=torch.uint8, device=dev) for _ in range(copies)]
+    for M in (1, 8, 32):
+        tot_b, tot_ms, per = 0, 0.0, {}
+        for name, (N, K) in layers.items():
+            ws = weights[name]
+            xq = torch.randint(0, 256, (fptq.fptq_packed_bytes(M, K),), dtype=torch.uint8, device=dev)
+            s_w = torch.rand(N, device=dev) * 0.015 + 0.005
+            y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            iters = 2 * len(ws)
+            fptq.fptq_w4a4_linear(xq, ws[0], M, N, K, 0.5, s_w, out=y)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            st = torch.cuda.Stream()
+            st.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.graph(g, stream=st):
+                for i in range(iters):
+                    fptq.fptq_w4a4_linear(xq, ws[i % len(ws)], M, N, K, 0.5, s_w, out=y)
+            g.replay()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(5):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / (5 * iters)
+            nbytes = len(ws[0]) + 4 * N + M * K // 2 + 2 * M * N
+            per[name] = {"us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1)}
+            tot_b += nbytes
+            tot_ms += ms
+            del g
+        gbs = tot_b / tot_ms / 1e6
+        res[f"M{M}"] = {"layer_us": round(tot_ms * 1e3, 2), "GBps": round(gbs, 1),
+                        "pct_hbm_peak": round(gbs / HBM_PEAK_GBS * 100, 2), "per_matrix": per}
+    return res
+
+
+if __name__ == "__main__":
+    main()
