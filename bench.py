@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode summary")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run one elementwise kernel that reads 1 GiB and writes 1 GiB: under rocprofv3 --pmc "
+                         "its FETCH_SIZE / WRITE_SIZE readings give the counter scale for a known byte count")
     return ap.parse_args()
 
 
@@ -56,6 +59,16 @@ def main():
 
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    if args.calibrate_copy:
+        # an elementwise kernel that reads 1 GiB and writes 1 GiB (a plain tensor copy may go through
+        # the DMA engines and would not show up as a kernel)
+        src = torch.full((1 << 28,), 3, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ workload: config c2
     gate, up, down = synth.config_cases("c2")

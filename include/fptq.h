@@ -110,6 +110,12 @@ int fptq_w4a4_linear(const void *xq_packed, const void *w_packed, int64_t M, int
 int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
                          const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream);
 
+/* Testing / tuning knob for the prefill kernel's tile shape (process-wide, not thread-safe against
+ * concurrent fptq_w4a4_linear calls): 0 = chosen per problem (default), 1 = 256x256, 2 = 192 (N) x
+ * 256 (M), 3 = 256 (N) x 128 (M), 4 = 256 x 128 with two workgroups per CU.  Results do not depend
+ * on it. */
+int fptq_set_gemm_tile(int tile);
+
 /* Library layout -> one int8 per value, [rows x K] row-major (for parity checks and debugging). */
 int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream);
 

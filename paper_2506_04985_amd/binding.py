@@ -17,7 +17,7 @@ ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4:
 
 # every symbol include/fptq.h declares
 EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
-           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack"]
+           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile"]
 
 _lib = None
 
@@ -48,6 +48,8 @@ def lib():
         for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p]
+        L.fptq_set_gemm_tile.restype = i32
+        L.fptq_set_gemm_tile.argtypes = [i32]
         L.fptq_unpack.restype = i32
         L.fptq_unpack.argtypes = [p, i64, i64, p, p]
         _lib = L
@@ -132,6 +134,10 @@ def fptq_w4a4_linear(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None, wa
 
 def fptq_w4a4_linear_ref(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None, want_acc=False, acc=None):
     return _linear(lib().fptq_w4a4_linear_ref, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc)
+
+
+def fptq_set_gemm_tile(tile):
+    _check(lib().fptq_set_gemm_tile(int(tile)))
 
 
 def fptq_unpack(packed, rows, K):

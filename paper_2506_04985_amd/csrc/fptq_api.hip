@@ -161,6 +161,16 @@ int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M,
                          row_out_scale, y_bf16, acc_dbg, stream);
 }
 
+int fptq_set_gemm_tile(int tile)
+{
+    if (tile < 0 || tile > 4) {
+        set_error("fptq_set_gemm_tile: tile must be 0..4");
+        return FPTQ_ERR_VALUE;
+    }
+    set_gemm_tile(tile);
+    return FPTQ_OK;
+}
+
 int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream)
 {
     if (!packed || !out_int8) {

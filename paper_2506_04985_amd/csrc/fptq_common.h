@@ -33,6 +33,8 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
 hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                                 const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s);
 
+void set_gemm_tile(int tile);
+
 // fp32 -> bf16 bit pattern, round to nearest even (NaN stays a quiet NaN)
 __device__ inline uint16_t bf16_rne(float f)
 {

@@ -14,6 +14,8 @@
 // descriptor's bounds check), STAGES-deep ring, one barrier per K tile -> ds_read_b128 fragments
 // -> widen -> MFMA.  The 16-byte granules of a row are XOR-swizzled in LDS so that the fragment
 // reads are bank-conflict free.
+#include <cmath>
+
 #include "fptq_common.h"
 
 namespace fptq {
@@ -30,9 +32,10 @@ constexpr int WAIT_LGKM0 = 15 | (3 << 14) | (7 << 4) | (0 << 8);
 // raw buffer descriptor, dword 3: 32-bit data format, no swizzle (gfx9 family encoding)
 constexpr int RSRC_FLAGS = 0x00020000;
 
-template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_>
+// OCC_ = workgroups meant to share a CU (caps the register budget: 512 / OCC_ per lane)
+template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_, int OCC_ = 1>
 struct GemmCfg {
-    static constexpr int WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, TN = TN_, TM = TM_, STAGES = STAGES_;
+    static constexpr int WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, TN = TN_, TM = TM_, STAGES = STAGES_, OCC = OCC_;
     static constexpr int BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32;
     static constexpr int WAVES = WAVES_N * WAVES_M, THREADS = 64 * WAVES;
     static constexpr int W_BYTES = BN * SEG, X_BYTES = BM * SEG, STAGE_BYTES = W_BYTES + X_BYTES;
@@ -41,8 +44,11 @@ struct GemmCfg {
     static constexpr int LOADS = W_LOADS + X_LOADS;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
     static_assert(W_BYTES % (WAVES * 1024) == 0 && X_BYTES % (WAVES * 1024) == 0, "tile must split over waves");
-    static_assert(W_LOADS == 4 && X_LOADS == 4, "the fill schedule below issues one W and one X chunk per quarter");
+    static_assert(W_LOADS >= 1 && W_LOADS <= 4 && X_LOADS >= 1 && X_LOADS <= 4, "the fill schedule issues at most one W and one X chunk per quarter");
+    // loads issued by fill quarters 0 and 1 (a quarter q carries W chunk q and X chunk q if they exist)
+    static constexpr int HALF_LOADS = (W_LOADS < 2 ? W_LOADS : 2) + (X_LOADS < 2 ? X_LOADS : 2);
     static_assert(STAGES >= 3, "pipeline needs three stages");
+    static_assert(TN <= 4, "a wave's channel run must fit 16 lanes of 8 channels in the epilogue");
 };
 
 // widen two packed dwords (16 nibbles) into one MFMA operand of 16 bytes, each 16 * value
@@ -76,7 +82,7 @@ __device__ inline void load_chunk(__amdgpu_buffer_rsrc_t r, uint8_t *lds_base, i
 }
 
 template <class C, bool ALIGNED, bool DUMP>
-__global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
+__global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, int tiles_m,
     int tiles_n, float s_a, const float *__restrict__ s_w, const float *__restrict__ d, uint16_t *__restrict__ y,
     int32_t *__restrict__ acc_out)
@@ -124,13 +130,22 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     auto x_desc = [&](int kt) {
         return __builtin_amdgcn_make_buffer_rsrc((void *)(xq + kt * x_slab), 0, (int)x_slab, RSRC_FLAGS);
     };
-    // quarter q (0..3) of the fill of one K tile: one W chunk and one X chunk
+    // quarter q (0..3) of the fill of one K tile: W chunk q and X chunk q, where they exist
     auto fill_quarter = [&](__amdgpu_buffer_rsrc_t wr, __amdgpu_buffer_rsrc_t xr, int stage, int q) {
         uint8_t *sb = lds + stage * C::STAGE_BYTES;
         if (q == 0) { load_chunk<0>(wr, sb + w_lds0, w_voff); load_chunk<0>(xr, sb + x_lds0, x_voff); }
-        if (q == 1) { load_chunk<1>(wr, sb + w_lds0, w_voff); load_chunk<1>(xr, sb + x_lds0, x_voff); }
-        if (q == 2) { load_chunk<2>(wr, sb + w_lds0, w_voff); load_chunk<2>(xr, sb + x_lds0, x_voff); }
-        if (q == 3) { load_chunk<3>(wr, sb + w_lds0, w_voff); load_chunk<3>(xr, sb + x_lds0, x_voff); }
+        if (q == 1) {
+            if (C::W_LOADS > 1) load_chunk<1>(wr, sb + w_lds0, w_voff);
+            if (C::X_LOADS > 1) load_chunk<1>(xr, sb + x_lds0, x_voff);
+        }
+        if (q == 2) {
+            if (C::W_LOADS > 2) load_chunk<2>(wr, sb + w_lds0, w_voff);
+            if (C::X_LOADS > 2) load_chunk<2>(xr, sb + x_lds0, x_voff);
+        }
+        if (q == 3) {
+            if (C::W_LOADS > 3) load_chunk<3>(wr, sb + w_lds0, w_voff);
+            if (C::X_LOADS > 3) load_chunk<3>(xr, sb + x_lds0, x_voff);
+        }
     };
 
     // ---- fragment read plan: lane (i = lane % 32, g = lane / 32) of a 32-row sub-tile reads, for
@@ -190,16 +205,17 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         }
     };
     // pin the interleave of one group: one MFMA, then its share of VALU work; an LDS read after
-    // every other MFMA when the group issues reads; the two fill loads in the middle
-    auto pin = [&](bool reads) {
-        constexpr int NM = C::TN * C::TM;
+    // the MFMAs that are followed by a widening when the group issues reads; the fill loads of
+    // quarter q in the middle
+    auto pin = [&](bool reads, int q) {
+        constexpr int NM = C::TN * C::TM, NOP = C::TN + C::TM, VPM = (6 * NOP + NM - 1) / NM;
+        const int n_vmem = (q < C::W_LOADS ? 1 : 0) + (q < C::X_LOADS ? 1 : 0);
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (reads && (i * (C::TN + C::TM)) / NM != ((i + 1) * (C::TN + C::TM)) / NM)
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (i == NM / 4 || i == (3 * NM) / 4) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            if (reads && (i * NOP) / NM != ((i + 1) * NOP) / NM) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if ((i == NM / 4 && n_vmem > 0) || (i == (3 * NM) / 4 && n_vmem > 1)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -216,7 +232,7 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
     __amdgpu_buffer_rsrc_t wr_b = w_desc(clampk(C::STAGES)), xr_b = x_desc(clampk(C::STAGES));
     fill_quarter(wr_a, xr_a, C::STAGES - 1, 0);
     fill_quarter(wr_a, xr_a, C::STAGES - 1, 1);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2) + C::LOADS / 2));   // tile 0 is in
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2) + C::HALF_LOADS));   // tile 0 is in
     __builtin_amdgcn_s_barrier();
     read_frags(0, 0, rawW[0], rawX[0]);
 #pragma unroll
@@ -233,11 +249,11 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         read_frags(stage, 1, rawW[1], rawX[1]);
         fill_quarter(wr_a, xr_a, stage_prev, 2);
         group(opW[0], opX[0], opW[1], opX[1], rawW[0], rawX[0], 1);
-        pin(true);
+        pin(true, 2);
         // G1
         fill_quarter(wr_a, xr_a, stage_prev, 3);
         group(opW[1], opX[1], opW[0], opX[0], rawW[1], rawX[1], 0);
-        pin(false);
+        pin(false, 3);
         // own loads of tile kt+1 have landed (younger: all of tiles kt+2 .. kt+S-1); the barrier
         // extends that to every wave's loads and says every wave is done reading tile kt
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2)));
@@ -247,7 +263,7 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         read_frags(stage_next, 0, rawW[0], rawX[0]);
         fill_quarter(wr_b, xr_b, stage, 0);
         group(opW[0], opX[0], opW[1], opX[1], rawW[1], rawX[1], 1);
-        pin(true);
+        pin(true, 0);
         // G3
         fill_quarter(wr_b, xr_b, stage, 1);
         wr_a = wr_b;
@@ -255,7 +271,7 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         wr_b = w_desc(clampk(kt + C::STAGES + 1));
         xr_b = x_desc(clampk(kt + C::STAGES + 1));
         group(opW[1], opX[1], opW[0], opX[0], rawW[0], rawX[0], 0);
-        pin(false);
+        pin(false, 1);
         stage = stage_next;
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the repeated tail loads before LDS is reused
@@ -301,13 +317,15 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_wave_barrier();
         // read back row segments: 16 bytes (8 channels) per lane, WN / 8 lanes per token row
-        constexpr int LANES_PER_ROW = WN / 8, ROWS_PER_PASS = 64 / LANES_PER_ROW;
+        // (lanes per row rounded up to a power of two; the surplus lanes idle)
+        constexpr int LANES_PER_ROW = WN / 8 <= 4 ? 4 : WN / 8 <= 8 ? 8 : 16, ROWS_PER_PASS = 64 / LANES_PER_ROW;
 #pragma unroll
         for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
             const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW, col = (lane % LANES_PER_ROW) * 8;
-            const uint4 v = *reinterpret_cast<const uint4 *>(patch + row * PATCH_STRIDE + col * 2);
+            const bool live = col < WN;
+            const uint4 v = live ? *reinterpret_cast<const uint4 *>(patch + row * PATCH_STRIDE + col * 2) : make_uint4(0, 0, 0, 0);
             const int mm = mw0 + row, nn = nw0 + col;
-            if (mm < M && nn < N) {
+            if (live && mm < M && nn < N) {
                 uint16_t *dst = y + (int64_t)mm * N + nn;
                 if (ALIGNED) {       // N % 8 == 0: the segment is whole and 16-byte aligned
                     *reinterpret_cast<uint4 *>(dst) = v;
@@ -334,6 +352,10 @@ __global__ __launch_bounds__(C::THREADS) void linear_mfma_kernel(
         }
     }
 }
+
+// 0 = choose the tile shape per problem; 1..4 = force one (testing and tuning)
+static int g_forced_tile = 0;
+void set_gemm_tile(int tile) { g_forced_tile = tile; }
 
 template <class C, bool ALIGNED, bool DUMP>
 static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
@@ -371,8 +393,31 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     // of all rows (rows * 64 bytes) must fit a 32-bit buffer descriptor.  Beyond them the simple
     // kernel answers.
     if (K > 131071 || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    typedef GemmCfg<2, 2, 4, 4, 4> Big;     // 256 x 256 tile, 4 waves of 128 x 128, 128 KB LDS
-    return launch_cfg<Big>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    // Tile shapes (all 4 waves, 4-stage ring).  The 256 x 256 tile has the best operand reuse; the
+    // other two exist for shapes whose 256 x 256 tile count fills the 256 CUs badly.
+    typedef GemmCfg<2, 2, 4, 4, 4> T256x256;   // waves of 128 x 128
+    typedef GemmCfg<2, 2, 3, 4, 4> T192x256;   // BN = 192: waves of 96 (n) x 128 (m)
+    typedef GemmCfg<2, 2, 4, 2, 4> T256x128;   // BM = 128: waves of 128 (n) x 64 (m)
+    typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;   // the same tile, two workgroups per CU
+    // Estimated time = tile waves over the 256 CUs x tile area x a per-shape factor fitted to
+    // measurements (smaller wave tiles spend more LDS reads and issue slots per MFMA).  With two
+    // workgroups per CU the tail is filled dynamically, so its wave count is not rounded up.
+    auto tiles = [&](int64_t bn, int64_t bm) { return (double)(((N + bn - 1) / bn) * ((M + bm - 1) / bm)); };
+    const double CUS = 256.0;
+    const double cost[4] = {
+        ceil(tiles(256, 256) / CUS) * 256.0 * 256.0,
+        ceil(tiles(192, 256) / CUS) * 192.0 * 256.0 * 1.06,
+        ceil(tiles(256, 128) / CUS) * 256.0 * 128.0 * 1.12,
+        fmax(1.0, tiles(256, 128) / (2 * CUS)) * 2.0 * 256.0 * 128.0 * 1.10,
+    };
+    int pick = g_forced_tile > 0 ? g_forced_tile - 1 : 0;
+    if (g_forced_tile <= 0)
+        for (int i = 1; i < 4; ++i)
+            if (cost[i] < cost[pick]) pick = i;
+    if (pick == 1) return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (pick == 2) return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
 }
 
 }  // namespace fptq

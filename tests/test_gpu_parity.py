@@ -106,6 +106,22 @@ def test_linear_matches_oracle(oracle, M, N, K, use_ref):
     assert np.array_equal(got["y"], ref["y"])          # same fp32 recipe on both sides: expected identical
 
 
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("M,N,K", [(128, 512, 512), (257, 513, 1024), (300, 260, 4096), (100, 300, 640), (33, 1000, 130),
+                                   (520, 390, 896)])
+def test_every_prefill_tile_shape(oracle, M, N, K, tile):
+    """Each tile shape of the MFMA kernel, forced, on shapes with ragged edges in M, N and K."""
+    inp = synth.draw(small_case(M, N, K, synth.MODE_RMS, seed=M + N + K + tile))
+    ref = oracle.w4a4_linear(inp.x_bits, inp.w_int, inp.s_a, inp.s_w, synth.MODE_RMS, inp.case.eps)
+    fptq.fptq_set_gemm_tile(tile)
+    try:
+        got = run_gpu_linear(inp)
+    finally:
+        fptq.fptq_set_gemm_tile(0)
+    assert np.array_equal(got["acc"], ref["acc"])
+    assert np.array_equal(got["y"], ref["y"])
+
+
 def test_config1_tiny(oracle):
     for case in synth.config_cases("c1"):
         inp = synth.draw(case)
