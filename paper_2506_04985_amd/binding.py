@@ -86,6 +86,11 @@ def fptq_packed_bytes(rows, K):
     return int(n)
 
 
+def _need(rows, K):
+    # same formula as the library's fptq_packed_bytes, kept in Python to spare a foreign call per argument check
+    return ((K + 127) // 128) * rows * 64
+
+
 def fptq_pack_weights(w_int, out=None):
     """int8 [N, K] device tensor with values in [-8, 7] -> packed uint8 blob."""
     _dev(w_int, torch.int8, "w_int")
@@ -103,7 +108,7 @@ def fptq_quantize_act(x_bf16, s_a, scale_mode=SCALE_RMS, eps=0.0, row_scale_in=N
     M, K = x_bf16.shape
     if row_scale_in is not None:
         _dev(row_scale_in, torch.float32, "row_scale_in")
-    out = torch.empty(fptq_packed_bytes(M, K), dtype=torch.uint8, device=x_bf16.device) if out is None else out
+    out = torch.empty(_need(M, K), dtype=torch.uint8, device=x_bf16.device) if out is None else out
     if row_scale_out is None and want_row_scale:
         row_scale_out = torch.empty(M, dtype=torch.float32, device=x_bf16.device)
     _check(lib().fptq_quantize_act(_ptr(x_bf16), M, K, scale_mode, float(eps), _ptr(row_scale_in), float(s_a),
@@ -115,7 +120,7 @@ def _linear(fn, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc):
     _dev(xq, torch.uint8, "xq")
     _dev(wq, torch.uint8, "wq")
     _dev(s_w, torch.float32, "s_w")
-    if xq.numel() < fptq_packed_bytes(M, K) or wq.numel() < fptq_packed_bytes(N, K) or s_w.numel() < N:
+    if xq.numel() < _need(M, K) or wq.numel() < _need(N, K) or s_w.numel() < N:
         raise FptqError(-3, "packed buffer or s_w smaller than the shape needs")
     if row_out_scale is not None:
         _dev(row_out_scale, torch.float32, "row_out_scale")

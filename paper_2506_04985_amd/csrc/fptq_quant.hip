@@ -1,9 +1,10 @@
 // Activation path of the quantized linear layer: per-token scale (Sec. 3.1.3 Step 1), static
 // per-tensor INT4 quantization (App. B) and nibble packing (App. J) in one pass over X.
 //
-// One workgroup per token row.  The row is read once from HBM and kept in registers while the
-// sum of squares is reduced, then quantized from the registers.  Bandwidth-bound: 2 bytes read
-// and half a byte written per element.
+// The row is read once from HBM and kept in registers while the sum of squares is reduced, then
+// quantized from the registers.  Bandwidth-bound: 2 bytes read and half a byte written per
+// element.  Rows up to 12288 values are handled by one wave each (no LDS, no barrier, the scale is
+// computed once per row, and many rows are in flight per CU); longer rows by one workgroup each.
 #include "fptq_common.h"
 
 namespace fptq {
@@ -120,12 +121,79 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
     }
 }
 
+// One wave per row, CH 16-byte chunks per lane (K <= 512 * CH, K % 8 == 0, 16-byte aligned rows).
+template <int MODE, int CH>
+__global__ __launch_bounds__(QT) void quantize_act_wave_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K, float eps,
+                                                               const float *__restrict__ row_in, float inv_s_a,
+                                                               uint8_t *__restrict__ out, float *__restrict__ row_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * (QT / 64) + (threadIdx.x >> 6);
+    if (t >= M) return;
+    const uint16_t *row = x + t * K;
+    const int64_t Kpad = k_tiles(K) * KT;
+
+    uint4 regs[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
+        regs[i] = k0 < K ? *reinterpret_cast<const uint4 *>(row + k0) : make_uint4(0, 0, 0, 0);
+    }
+    float r = 1.0f;
+    if (MODE == FPTQ_SCALE_RMS) {
+        double ss = 0.0;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                double a = (double)bf16_to_f32(w[j] & 0xffffu), b = (double)bf16_to_f32(w[j] >> 16);
+                ss += a * a;
+                ss += b * b;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        r = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
+    } else if (MODE == FPTQ_SCALE_GIVEN) {
+        r = row_in[t];
+    }
+    const float c = (MODE == FPTQ_SCALE_NONE) ? inv_s_a : r * inv_s_a;
+    if (lane == 0 && row_out) row_out[t] = r;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
+        if (k0 < Kpad) {
+            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+            uint32_t word = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c) << (8 * j);
+                word |= quant_nibble(bf16_to_f32(w[j] >> 16), c) << (8 * j + 4);
+            }
+            store_word(out, M, t, k0, k0 < K ? word : 0u);     // K padding stays zero
+        }
+    }
+}
+
 template <int MODE>
 static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps, const float *row_in, float inv_s_a,
                               uint8_t *out, float *row_out, hipStream_t s)
 {
     dim3 grid((unsigned)M), block(QT);
-    if (K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0)
+    const bool vec = K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+    const int64_t Kpad = k_tiles(K) * KT;
+    if (vec && Kpad <= 512 * 24) {
+        dim3 wgrid((unsigned)((M + QT / 64 - 1) / (QT / 64)));
+        if (Kpad <= 512 * 8)
+            quantize_act_wave_kernel<MODE, 8><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+        else if (Kpad <= 512 * 16)
+            quantize_act_wave_kernel<MODE, 16><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+        else
+            quantize_act_wave_kernel<MODE, 24><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+        return hipGetLastError();
+    }
+    if (vec)
         quantize_act_kernel<MODE, true><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
     else
         quantize_act_kernel<MODE, false><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
