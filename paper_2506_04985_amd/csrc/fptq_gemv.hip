@@ -3,7 +3,7 @@
 //
 // The job is bound by reading the packed weights once from HBM, so the kernel is built around
 // keeping many weight loads in flight per CU and doing as little else as possible:
-//   - a workgroup owns 16 output channels; its WAVES waves split K (wave w takes K tiles
+//   - a workgroup owns 16 (or 32) output channels; its WAVES waves split K (wave w takes K tiles
 //     w, w + WAVES, ...), so even the smallest matrices give every CU a workgroup, and several
 //     workgroups fit a CU (no LDS ring, few registers), which overlaps their ramp-up and tails;
 //   - weights go HBM -> registers directly in MFMA operand order: lane (i = l % 16, g = l / 16)
@@ -31,37 +31,46 @@ __device__ inline v4i dec_widen(int p0, int p1)
     return o;
 }
 
-// MT = number of 16-token groups (1: M <= 16, 2: M <= 32); U = K tiles in flight per wave
-template <int WAVES, int U, int MT>
+// MT = number of 16-token groups (1: M <= 16, 2: M <= 32); RT = number of 16-channel groups per
+// workgroup (2 halves the activation re-reads per weight byte, used when M > 16 and N is large);
+// U = K tiles in flight per wave
+template <int WAVES, int U, int MT, int RT>
 __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, float s_a,
     const float *__restrict__ s_w, const float *__restrict__ d, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
 {
-    __shared__ int32_t red[WAVES * MT * 256];          // [WAVES][MT][16 tokens][16 channels]
+    __shared__ int32_t red[WAVES * RT * MT * 256];     // [WAVES][RT][MT][16 tokens][16 channels]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n0 = blockIdx.x * 16;
+    const int n0 = blockIdx.x * (16 * RT);
     const int fi = lane & 15, fg = lane >> 4;
 
     // lane (i, g): granule g of weight row n0 + i, and of token row i (clamped: rows past the end
     // repeat the last one; what they produce is never stored).  The low 8 bytes of a granule feed
     // the first MFMA of the K tile (k = 32 g + 0..15), the high 8 bytes the second.
     const int64_t w_slab = (int64_t)N * SEG, x_slab = (int64_t)M * SEG;
-    const uint8_t *wp = wq + (int64_t)min(n0 + fi, N - 1) * SEG + fg * 16;
-    const uint8_t *xp[MT];
+    const uint8_t *wp[RT], *xp[MT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) wp[rt] = wq + (int64_t)min(n0 + rt * 16 + fi, N - 1) * SEG + fg * 16;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) xp[mt] = xq + (int64_t)min(mt * 16 + fi, M - 1) * SEG + fg * 16;
 
     const int T = wave < ktiles ? (ktiles - wave + WAVES - 1) / WAVES : 0;   // K tiles of this wave
-    v4i acc[MT];
+    v4i acc[RT][MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = v4i{0, 0, 0, 0};
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = v4i{0, 0, 0, 0};
 
     for (int base = 0; base < T; base += U) {
-        v4i wv[U], xv[MT][U];
+        v4i wv[RT][U], xv[MT][U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (base + u < T) wv[u] = *reinterpret_cast<const v4i *>(wp + (int64_t)(wave + (base + u) * WAVES) * w_slab);
+            if (base + u < T) {
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    wv[rt][u] = *reinterpret_cast<const v4i *>(wp[rt] + (int64_t)(wave + (base + u) * WAVES) * w_slab);
+            }
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (base + u < T) {
@@ -72,12 +81,20 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (base + u < T) {
-                const v4i w0 = dec_widen(wv[u][0], wv[u][1]), w1 = dec_widen(wv[u][2], wv[u][3]);
+                v4i x0[MT], x1[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    const v4i x0 = dec_widen(xv[mt][u][0], xv[mt][u][1]), x1 = dec_widen(xv[mt][u][2], xv[mt][u][3]);
-                    acc[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, x0, acc[mt], 0, 0, 0);
-                    acc[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1, x1, acc[mt], 0, 0, 0);
+                    x0[mt] = dec_widen(xv[mt][u][0], xv[mt][u][1]);
+                    x1[mt] = dec_widen(xv[mt][u][2], xv[mt][u][3]);
+                }
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    const v4i w0 = dec_widen(wv[rt][u][0], wv[rt][u][1]), w1 = dec_widen(wv[rt][u][2], wv[rt][u][3]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        acc[rt][mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, x0[mt], acc[rt][mt], 0, 0, 0);
+                        acc[rt][mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1, x1[mt], acc[rt][mt], 0, 0, 0);
+                    }
                 }
             }
     }
@@ -85,16 +102,19 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
     // ---- reduce the WAVES partial tiles through LDS.  D layout of the 16x16 MFMA: lane l, register
     // r holds D[row = 4 (l / 16) + r][col = l % 16]; rows are output channels, columns tokens.
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[((wave * MT + mt) * 16 + fi) * 16 + 4 * fg + r] = acc[mt][r];
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                red[(((wave * RT + rt) * MT + mt) * 16 + fi) * 16 + 4 * fg + r] = acc[rt][mt][r];
     __syncthreads();
-    for (int o = tid; o < MT * 256; o += 64 * WAVES) {
-        const int mt = o >> 8, j = (o >> 4) & 15, i = o & 15;     // token group, token, channel
+    for (int o = tid; o < RT * MT * 256; o += 64 * WAVES) {
+        const int g = o >> 8, rt = g / MT, mt = g % MT, j = (o >> 4) & 15, i = o & 15;   // groups, token, channel
         int32_t sum = 0;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) sum += red[((w * MT + mt) * 16 + j) * 16 + i];
-        const int t = mt * 16 + j, n = n0 + i;
+        for (int w = 0; w < WAVES; ++w) sum += red[(((w * RT + rt) * MT + mt) * 16 + j) * 16 + i];
+        const int t = mt * 16 + j, n = n0 + rt * 16 + i;
         if (t < M && n < N) {
             const int32_t a = sum >> 8;                // exact: the sum is 256 * acc
             y[(int64_t)t * N + n] = dequant_bf16(a, s_a * s_w[n], d, t);
@@ -103,11 +123,11 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
     }
 }
 
-template <int WAVES, int U, int MT>
+template <int WAVES, int U, int MT, int RT>
 static hipError_t launch_decode_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                                     const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
 {
-    linear_decode_kernel<WAVES, U, MT><<<dim3((unsigned)((N + 15) / 16)), dim3(64 * WAVES), 0, s>>>(
+    linear_decode_kernel<WAVES, U, MT, RT><<<dim3((unsigned)((N + 16 * RT - 1) / (16 * RT))), dim3(64 * WAVES), 0, s>>>(
         xq, wq, (int)M, (int)N, (int)k_tiles(K), s_a, s_w, d, y, acc);
     return hipGetLastError();
 }
@@ -117,8 +137,16 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
 {
     // Limits: M <= 32; 256 * acc must stay in int32; the grid is one workgroup per 16 channels.
     if (M > 32 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    if (M <= 16) return launch_decode_cfg<8, 8, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    return launch_decode_cfg<8, 8, 2>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    // K split: 16 waves per workgroup when K is long (each wave keeps at least four K tiles), so that
+    // small-N / large-K matrices still put enough loads in flight on every CU; 8 otherwise.
+    const bool wide = k_tiles(K) >= 64;
+    if (M <= 16) {
+        if (wide) return launch_decode_cfg<16, 8, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+        return launch_decode_cfg<8, 4, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    }
+    if (N >= 16384) return launch_decode_cfg<8, 4, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (wide) return launch_decode_cfg<16, 8, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    return launch_decode_cfg<8, 4, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
 }
 
 }  // namespace fptq
