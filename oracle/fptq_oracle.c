@@ -206,6 +206,53 @@ int oracle_epilogue(const int32_t *acc, int64_t M, int64_t N, float s_a, const f
     return 0;
 }
 
+/* App. D "Hadamard non-powers of 2": the online transform in front of the down projection is a
+ * block-wise Walsh-Hadamard transform, H_B = kron of [[1, 1], [1, -1]], applied to consecutive
+ * blocks of B = 2^n channels and scaled by 1 / sqrt(B).  Evaluated here by the textbook in-place
+ * butterfly network in fp32, strides h = B/2, B/4, ..., 1, each pair (a, b) -> (a + b, a - b).
+ * The result is the unnormalised transform; the 1 / sqrt(B) goes into the quantizer's multiplier. */
+static void fwht_block_f32(float *x, int64_t B)
+{
+    for (int64_t h = B / 2; h >= 1; h /= 2)
+        for (int64_t i = 0; i < B; i += 2 * h)
+            for (int64_t j = i; j < i + h; ++j) {
+                float a = x[j], b = x[j + h];
+                x[j] = a + b;
+                x[j + h] = a - b;
+            }
+}
+
+int oracle_hadamard_rows(const uint16_t *x, int64_t M, int64_t K, int64_t B, float *out)
+{
+    if (B < 1 || (B & (B - 1)) || K % B) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < M; ++t) {
+        float *row = out + t * K;
+        for (int64_t k = 0; k < K; ++k) row[k] = bf16_bits_to_f32(x[t * K + k]);
+        for (int64_t k0 = 0; k0 < K; k0 += B) fwht_block_f32(row + k0, B);
+    }
+    return 0;
+}
+
+/* multiplier of the Hadamard path: c_t = (S_t * (1 / s_a)) * (float)(1 / sqrt(B)), two fp32 products */
+float oracle_hadamard_multiplier(float row_scale, float s_a, int has_row_scale, int64_t B)
+{
+    float hn = (float)(1.0 / sqrt((double)B));
+    return oracle_row_multiplier(row_scale, s_a, has_row_scale) * hn;
+}
+
+/* Hadamard, then the static quantizer: q = clamp(rne(h * c_t), -8, 7) on the transformed row.
+ * h [M x K] fp32 is what oracle_hadamard_rows produced. */
+int oracle_quantize_f32(const float *h, int64_t M, int64_t K, const float *row_scale, float s_a, int64_t B, int8_t *q)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < M; ++t) {
+        float c = oracle_hadamard_multiplier(row_scale ? row_scale[t] : 1.0f, s_a, row_scale != NULL, B);
+        for (int64_t k = 0; k < K; ++k) q[t * K + k] = quantize_one(h[t * K + k], c);
+    }
+    return 0;
+}
+
 /* Whole path for the timed baseline: row scale -> quantize -> int32 GEMM -> epilogue.
  * Scratch (q [M x K] int8, acc [M x N] int32, r [M] float) is the caller's. */
 int oracle_w4a4_linear(const uint16_t *x, const int8_t *w, int64_t M, int64_t N, int64_t K, int mode, float eps,

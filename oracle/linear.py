@@ -54,6 +54,12 @@ def lib():
         L.oracle_epilogue.argtypes = [p, i64, i64, f32, p, p, p]
         L.oracle_w4a4_linear.restype = ctypes.c_int
         L.oracle_w4a4_linear.argtypes = [p, p, i64, i64, i64, ctypes.c_int, f32, p, f32, p, p, p, p, p, p]
+        L.oracle_hadamard_rows.restype = ctypes.c_int
+        L.oracle_hadamard_rows.argtypes = [p, i64, i64, i64, p]
+        L.oracle_hadamard_multiplier.restype = f32
+        L.oracle_hadamard_multiplier.argtypes = [f32, f32, ctypes.c_int, i64]
+        L.oracle_quantize_f32.restype = ctypes.c_int
+        L.oracle_quantize_f32.argtypes = [p, i64, i64, p, f32, i64, p]
         L.oracle_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -93,6 +99,26 @@ def quantize(x_bits, s_a, row_scale=None):
     q = np.empty((M, K), dtype=np.int8)
     r = None if row_scale is None else _c(row_scale, np.float32)
     lib().oracle_quantize(_ptr(x_bits), M, K, _ptr(r), float(np.float32(s_a)), _ptr(q))
+    return q
+
+
+def hadamard_rows(x_bits, block):
+    """App. D block-wise Walsh-Hadamard transform of every row (unnormalised, fp32 butterflies)."""
+    x_bits = _c(x_bits, np.uint16)
+    M, K = x_bits.shape
+    out = np.empty((M, K), dtype=np.float32)
+    if lib().oracle_hadamard_rows(_ptr(x_bits), M, K, int(block), _ptr(out)):
+        raise ValueError("block must be a power of two dividing K")
+    return out
+
+
+def quantize_hadamard(x_bits, s_a, block, row_scale=None):
+    """Online Hadamard (Sec. 3.1.4, App. D) followed by the static quantizer (App. B): int8 [M, K]."""
+    h = hadamard_rows(x_bits, block)
+    M, K = h.shape
+    q = np.empty((M, K), dtype=np.int8)
+    r = None if row_scale is None else _c(row_scale, np.float32)
+    lib().oracle_quantize_f32(_ptr(h), M, K, _ptr(r), float(np.float32(s_a)), int(block), _ptr(q))
     return q
 
 

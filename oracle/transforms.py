@@ -10,6 +10,7 @@ Passages followed:
   multi-head value transform (T_v)        Sec. 3.1.2
   per-token residual scaling S_n          Sec. 3.1.3, Eq. (5)-(7)
   RMSNorm gain folded into the next linear  Sec. 4.1 (transforms and norm scales are merged)
+  online Hadamard T_d before the down projection, block-wise for non-powers of 2   Sec. 3.1.4, App. D
   round-to-nearest weight quantization    Sec. 4 "RTN", App. D
 
 Readings where the text is inconsistent:
@@ -202,6 +203,32 @@ def scaled_residual_stack(X1, blocks):
         Zts.append(Zt)
         S_prev, Zt_prev = S, Zt
     return Ss, Zts
+
+
+# ----------------------------------------------------------------------------- online Hadamard T_d
+def hadamard_matrix(n):
+    """H_n = kron of [[1, 1], [1, -1]] (App. D), n a power of two; unnormalised."""
+    H = np.ones((1, 1))
+    while H.shape[0] < n:
+        H = np.kron(H, np.array([[1.0, 1.0], [1.0, -1.0]]))
+    assert H.shape[0] == n
+    return H
+
+
+def block_hadamard_matrix(K, block):
+    """T_d for a width that is not a power of two: blockdiag of H_block / sqrt(block) (App. D)."""
+    assert K % block == 0
+    return block_diag([hadamard_matrix(block) / np.sqrt(block)] * (K // block))
+
+
+def merge_hadamard_down(Wd, block):
+    """W~_d = T_d^T W_d for y = x W_d with W_d [d_ff, d_model]: (x T_d)(T_d^T W_d) = x W_d."""
+    Td = block_hadamard_matrix(Wd.shape[0], block)
+    return Td.T @ Wd
+
+
+def largest_pow2_divisor(K):
+    return K & (-K)
 
 
 # ----------------------------------------------------------------------------- weight quantizer
