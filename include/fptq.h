@@ -87,6 +87,21 @@ int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, 
                       float *row_scale_out, void *stream);
 
 /*
+ * The same with the online Hadamard transform T_d in front of the quantizer (Sec. 3.1.4; App. D,
+ * "Hadamard non-powers of 2"): every row is transformed block-wise, x' = x blockdiag(H_B / sqrt(B)),
+ * then scaled, quantized and packed as above.  The inverse is merged into the weights offline.
+ *   hadamard_block  B, a power of two dividing K.  This build implements B = 256 (the group size the
+ *                   paper reports for the Llama-2 FFN width 11008 = 43 * 256); anything else, or a K
+ *                   that 256 does not divide, returns FPTQ_ERR_SHAPE.  x_bf16 must be 16-byte aligned.
+ *   FPTQ_SCALE_RMS takes S_t from the untransformed row (what the norm layer computes).
+ * Arithmetic: in-place butterflies in fp32 with strides B/2, ..., 1, each pair (a, b) -> (a + b, a - b);
+ * c_t = (S_t * (1.0f / s_a)) * (float)(1 / sqrt(B)); q = clamp(rne(h * c_t), -8, 7).
+ */
+int fptq_quantize_act_hadamard(const void *x_bf16, int64_t M, int64_t K, int hadamard_block, int scale_mode, float eps,
+                               const float *row_scale_in, float s_a, void *xq_packed, int64_t xq_bytes,
+                               float *row_scale_out, void *stream);
+
+/*
  * The quantized linear layer proper: INT4 x INT4 matmul with INT32 accumulation and the
  * float-scale epilogue (App. J; App. B).  Picks a few-token (bandwidth-bound) kernel for small M
  * and the INT8-MFMA GEMM otherwise.

@@ -17,6 +17,7 @@ ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4:
 
 # every symbol include/fptq.h declares
 EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
+           "fptq_quantize_act_hadamard",
            "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile"]
 
 _lib = None
@@ -45,6 +46,8 @@ def lib():
         L.fptq_pack_weights.argtypes = [p, i64, i64, p, i64, p]
         L.fptq_quantize_act.restype = i32
         L.fptq_quantize_act.argtypes = [p, i64, i64, i32, f32, p, f32, p, i64, p, p]
+        L.fptq_quantize_act_hadamard.restype = i32
+        L.fptq_quantize_act_hadamard.argtypes = [p, i64, i64, i32, i32, f32, p, f32, p, i64, p, p]
         for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p]
@@ -113,6 +116,22 @@ def fptq_quantize_act(x_bf16, s_a, scale_mode=SCALE_RMS, eps=0.0, row_scale_in=N
         row_scale_out = torch.empty(M, dtype=torch.float32, device=x_bf16.device)
     _check(lib().fptq_quantize_act(_ptr(x_bf16), M, K, scale_mode, float(eps), _ptr(row_scale_in), float(s_a),
                                    _ptr(out), out.numel(), _ptr(row_scale_out), _stream()))
+    return out, row_scale_out
+
+
+def fptq_quantize_act_hadamard(x_bf16, s_a, hadamard_block=256, scale_mode=SCALE_GIVEN, eps=0.0, row_scale_in=None, out=None,
+                               row_scale_out=None, want_row_scale=True):
+    """bf16 [M, K] -> block-wise Hadamard, per-token scale, static INT4 quantizer, packed."""
+    _dev(x_bf16, torch.bfloat16, "x_bf16")
+    M, K = x_bf16.shape
+    if row_scale_in is not None:
+        _dev(row_scale_in, torch.float32, "row_scale_in")
+    out = torch.empty(_need(M, K), dtype=torch.uint8, device=x_bf16.device) if out is None else out
+    if row_scale_out is None and want_row_scale:
+        row_scale_out = torch.empty(M, dtype=torch.float32, device=x_bf16.device)
+    _check(lib().fptq_quantize_act_hadamard(_ptr(x_bf16), M, K, int(hadamard_block), scale_mode, float(eps),
+                                            _ptr(row_scale_in), float(s_a), _ptr(out), out.numel(), _ptr(row_scale_out),
+                                            _stream()))
     return out, row_scale_out
 
 

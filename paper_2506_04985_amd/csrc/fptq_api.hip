@@ -109,42 +109,66 @@ int fptq_pack_weights(const int8_t *w_int, int64_t N, int64_t K, void *w_packed,
     return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_pack_weights", e);
 }
 
-int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, float eps, const float *row_scale_in,
-                      float s_a, void *xq_packed, int64_t xq_bytes, float *row_scale_out, void *stream)
+static int quantize_common(const char *fn, int hadamard_block, const void *x_bf16, int64_t M, int64_t K, int scale_mode,
+                           float eps, const float *row_scale_in, float s_a, void *xq_packed, int64_t xq_bytes,
+                           float *row_scale_out, void *stream)
 {
     if (!x_bf16 || !xq_packed) {
-        set_error("fptq_quantize_act: NULL pointer");
+        set_error("%s: NULL pointer", fn);
         return FPTQ_ERR_NULL;
     }
-    int rc = check_dims("fptq_quantize_act", M, K, "M", "K");
+    int rc = check_dims(fn, M, K, "M", "K");
     if (rc) return rc;
+    if (hadamard_block != 0 && (hadamard_block != 256 || K % 256 != 0)) {
+        set_error("%s: hadamard_block must be 256 and divide K (got block %d, K %lld)", fn, hadamard_block, (long long)K);
+        return FPTQ_ERR_SHAPE;
+    }
     if (scale_mode != FPTQ_SCALE_NONE && scale_mode != FPTQ_SCALE_RMS && scale_mode != FPTQ_SCALE_GIVEN) {
-        set_error("fptq_quantize_act: unknown scale_mode %d", scale_mode);
+        set_error("%s: unknown scale_mode %d", fn, scale_mode);
         return FPTQ_ERR_MODE;
     }
     if (scale_mode == FPTQ_SCALE_GIVEN && !row_scale_in) {
-        set_error("fptq_quantize_act: FPTQ_SCALE_GIVEN needs row_scale_in");
+        set_error("%s: FPTQ_SCALE_GIVEN needs row_scale_in", fn);
         return FPTQ_ERR_MODE;
     }
     if (!(s_a > 0.0f) || !std::isfinite(s_a) || !(eps >= 0.0f)) {
-        set_error("fptq_quantize_act: s_a must be finite and > 0, eps >= 0");
+        set_error("%s: s_a must be finite and > 0, eps >= 0", fn);
         return FPTQ_ERR_VALUE;
     }
     if (xq_bytes < packed_bytes(M, K)) {
-        set_error("fptq_quantize_act: buffer of %lld bytes, need %lld", (long long)xq_bytes,
-                  (long long)packed_bytes(M, K));
+        set_error("%s: buffer of %lld bytes, need %lld", fn, (long long)xq_bytes, (long long)packed_bytes(M, K));
         return FPTQ_ERR_SIZE;
     }
-    if ((rc = check_align("fptq_quantize_act", xq_packed, 16, "xq_packed")) ||
-        (rc = check_align("fptq_quantize_act", x_bf16, 2, "x_bf16")) ||
-        (rc = check_align("fptq_quantize_act", row_scale_in, 4, "row_scale_in")) ||
-        (rc = check_align("fptq_quantize_act", row_scale_out, 4, "row_scale_out")))
+    if ((rc = check_align(fn, xq_packed, 16, "xq_packed")) || (rc = check_align(fn, x_bf16, hadamard_block ? 16 : 2, "x_bf16")) ||
+        (rc = check_align(fn, row_scale_in, 4, "row_scale_in")) || (rc = check_align(fn, row_scale_out, 4, "row_scale_out")))
         return rc;
     // the one fp32 division of the quantizer happens here, on the host
     volatile float inv = 1.0f / s_a;
-    hipError_t e = launch_quantize_act((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv,
-                                       (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream);
-    return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_quantize_act", e);
+    hipError_t e = hadamard_block
+                       ? launch_quantize_act_hadamard((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv,
+                                                      (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream)
+                       : launch_quantize_act((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv,
+                                             (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
+}
+
+int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, float eps, const float *row_scale_in,
+                      float s_a, void *xq_packed, int64_t xq_bytes, float *row_scale_out, void *stream)
+{
+    return quantize_common("fptq_quantize_act", 0, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a, xq_packed, xq_bytes,
+                           row_scale_out, stream);
+}
+
+int fptq_quantize_act_hadamard(const void *x_bf16, int64_t M, int64_t K, int hadamard_block, int scale_mode, float eps,
+                               const float *row_scale_in, float s_a, void *xq_packed, int64_t xq_bytes,
+                               float *row_scale_out, void *stream)
+{
+    if (hadamard_block == 0) {
+        set_error("fptq_quantize_act_hadamard: hadamard_block must be 256");
+        return FPTQ_ERR_SHAPE;
+    }
+    return quantize_common("fptq_quantize_act_hadamard", hadamard_block, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a,
+                           xq_packed, xq_bytes, row_scale_out, stream);
 }
 
 int fptq_w4a4_linear(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,

@@ -1,0 +1,82 @@
+"""GPU parity of the fused online-Hadamard quantizer (Sec. 3.1.4, App. D) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import transforms as T
+from paper_2506_04985_amd import binding as fptq
+from paper_2506_04985_amd import synth
+
+from gpu_util import dev, dev_bf16, host_bits, y_error, Y_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def case(M, K, mode, seed):
+    return synth.LinearCase("h", f"m{M}k{K}", M, 8, K, "normal", 0.0, 3, 20.0, mode, seed)
+
+
+@pytest.mark.parametrize("mode", [synth.MODE_NONE, synth.MODE_RMS, synth.MODE_GIVEN])
+@pytest.mark.parametrize("M,K", [(1, 256), (3, 512), (5, 768), (7, 1024), (4, 1280), (64, 4096), (9, 11008), (3, 14336),
+                                 (2, 28672), (130, 2304)])
+def test_hadamard_quantizer_bit_exact(oracle, mode, M, K):
+    inp = synth.draw(case(M, K, mode, seed=M * 3 + K), with_weights=False)
+    xb = inp.x_bits
+    # static scale for the transformed tensor: absmax of (S x) H / 16 over this draw, divided by 7
+    r_ref = oracle.row_scale(xb, mode, 1e-5, inp.row_scale_in)
+    h = oracle.hadamard_rows(xb, 256).astype(np.float64) / 16.0
+    if mode != synth.MODE_NONE:
+        h = h * r_ref.astype(np.float64)[:, None]
+    s_a = np.float32(np.abs(h).max() / 7.0 * 0.6)         # 0.6: make the clamp fire
+    xq, r = fptq.fptq_quantize_act_hadamard(dev_bf16(xb), float(s_a), 256, mode, 1e-5, dev(inp.row_scale_in))
+    q = fptq.fptq_unpack(xq, M, K).cpu().numpy()
+    q_ref = oracle.quantize_hadamard(xb, s_a, 256, None if mode == synth.MODE_NONE else r_ref)
+    assert np.array_equal(r.cpu().numpy().view(np.uint32), r_ref.view(np.uint32))
+    assert np.array_equal(q, q_ref)
+    assert q_ref.min() == -8 and q_ref.max() == 7 and (q_ref != 0).mean() > 0.3
+
+
+def test_hadamard_path_is_function_preserving_end_to_end(oracle):
+    """x W_d computed as quantize(x T_d) against quantize(T_d^T W_d): integer accumulators bit-exact against the
+    oracle, and the dequantised output close to the float product although x has outlier channels."""
+    rng = np.random.default_rng(11)
+    M, K, N = 96, 11008 // 43 * 5, 320             # K = 1280 = 5 blocks of 256
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, 6, replace=False)] *= 25.0
+    xb = synth.f32_to_bf16_bits(x)
+    Wd = rng.standard_normal((K, N)) / 16                       # paper convention: y = x W_d
+    w_int, s_w = T.rtn_weights(T.to_out_in(T.merge_hadamard_down(Wd, 256)))
+    h = oracle.hadamard_rows(xb, 256).astype(np.float64) / 16.0
+    s_a = np.float32(np.abs(h).max() / 7.0)
+    xq, _ = fptq.fptq_quantize_act_hadamard(dev_bf16(xb), float(s_a), 256, synth.MODE_NONE)
+    wq = fptq.fptq_pack_weights(dev(w_int))
+    y, acc = fptq.fptq_w4a4_linear(xq, wq, M, N, K, float(s_a), dev(s_w), want_acc=True)
+    q_ref = oracle.quantize_hadamard(xb, s_a, 256)
+    acc_ref = oracle.gemm_i64(q_ref, w_int).astype(np.int32)
+    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    y_ref = oracle.epilogue(acc_ref, s_a, s_w)
+    assert y_error(host_bits(y), y_ref) <= Y_TOL
+    y_fp = synth.bf16_bits_to_f32(xb).astype(np.float64) @ Wd
+    yg = synth.bf16_bits_to_f32(host_bits(y)).astype(np.float64)
+    rel_h = np.linalg.norm(yg - y_fp) / np.linalg.norm(y_fp)
+    # the same layer without the transform: the outlier channels eat the 4-bit grid
+    w0, s_w0 = T.rtn_weights(T.to_out_in(Wd))
+    s_a0 = np.float32(np.abs(synth.bf16_bits_to_f32(xb)).max() / 7.0)
+    base = oracle.w4a4_linear(xb, w0, s_a0, s_w0, oracle.MODE_NONE)
+    rel_0 = np.linalg.norm(synth.bf16_bits_to_f32(base["y"]).astype(np.float64) - y_fp) / np.linalg.norm(y_fp)
+    assert rel_h < 0.35 and rel_h < 0.5 * rel_0
+
+
+def test_hadamard_shape_errors():
+    x = torch.zeros((4, 384), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fptq.FptqError) as e:
+        fptq.fptq_quantize_act_hadamard(x, 1.0, 256, synth.MODE_NONE)      # 256 does not divide 384
+    assert e.value.code == -2
+    x = torch.zeros((4, 512), dtype=torch.bfloat16, device="cuda")
+    for blk in (0, 128, 512):
+        with pytest.raises(fptq.FptqError) as e:
+            fptq.fptq_quantize_act_hadamard(x, 1.0, blk, synth.MODE_NONE)
+        assert e.value.code == -2
+    with pytest.raises(fptq.FptqError) as e:
+        fptq.fptq_quantize_act_hadamard(x, 1.0, 256, synth.MODE_GIVEN, 0.0, None)
+    assert e.value.code == -4
