@@ -253,6 +253,28 @@ int oracle_quantize_f32(const float *h, int64_t M, int64_t K, const float *row_s
     return 0;
 }
 
+/* App. B "Dynamic quantization": the scale factor is computed at run time for each token
+ * independently, from that token's range.  With the symmetric 4-bit grid: s_t = max_k |x_t,k| / 7,
+ * q = clamp(rne(x * (1 / s_t)), -8, 7).  NaNs do not enter the maximum; an all-zero (or infinite)
+ * row gets s_t = 1.  Arithmetic in fp32: one division for s_t, one for its reciprocal, one
+ * multiply per element. */
+int oracle_quantize_dynamic(const uint16_t *x, int64_t M, int64_t K, float *s_out, int8_t *q)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < M; ++t) {
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            float v = fabsf(bf16_bits_to_f32(x[t * K + k]));
+            if (v == v && v > amax) amax = v;
+        }
+        float s = (amax > 0.0f && amax < INFINITY) ? amax / 7.0f : 1.0f;
+        float c = 1.0f / s;
+        s_out[t] = s;
+        for (int64_t k = 0; k < K; ++k) q[t * K + k] = quantize_one(bf16_bits_to_f32(x[t * K + k]), c);
+    }
+    return 0;
+}
+
 /* Whole path for the timed baseline: row scale -> quantize -> int32 GEMM -> epilogue.
  * Scratch (q [M x K] int8, acc [M x N] int32, r [M] float) is the caller's. */
 int oracle_w4a4_linear(const uint16_t *x, const int8_t *w, int64_t M, int64_t N, int64_t K, int mode, float eps,

@@ -60,6 +60,8 @@ def lib():
         L.oracle_hadamard_multiplier.argtypes = [f32, f32, ctypes.c_int, i64]
         L.oracle_quantize_f32.restype = ctypes.c_int
         L.oracle_quantize_f32.argtypes = [p, i64, i64, p, f32, i64, p]
+        L.oracle_quantize_dynamic.restype = ctypes.c_int
+        L.oracle_quantize_dynamic.argtypes = [p, i64, i64, p, p]
         L.oracle_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -120,6 +122,16 @@ def quantize_hadamard(x_bits, s_a, block, row_scale=None):
     r = None if row_scale is None else _c(row_scale, np.float32)
     lib().oracle_quantize_f32(_ptr(h), M, K, _ptr(r), float(np.float32(s_a)), int(block), _ptr(q))
     return q
+
+
+def quantize_dynamic(x_bits):
+    """App. B dynamic quantization: per-token s_t = max|x_t| / 7 at run time; returns (int8 [M, K], fp32 [M])."""
+    x_bits = _c(x_bits, np.uint16)
+    M, K = x_bits.shape
+    q = np.empty((M, K), dtype=np.int8)
+    s = np.empty(M, dtype=np.float32)
+    lib().oracle_quantize_dynamic(_ptr(x_bits), M, K, _ptr(s), _ptr(q))
+    return q, s
 
 
 def pack(v):
