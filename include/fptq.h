@@ -102,6 +102,18 @@ int fptq_quantize_act_hadamard(const void *x_bf16, int64_t M, int64_t K, int had
                                float *row_scale_out, void *stream);
 
 /*
+ * Dynamic activation quantization (App. B "Dynamic quantization"; the paper's second run-time
+ * setting, App. J "Dynamic INT4 runtime"): the scale is computed per token at run time,
+ *     s_t = max_k |x_t,k| / 7,   q = clamp(rne(x * (1 / s_t)), -8, 7)    (fp32; NaNs ignored in the
+ * maximum; a zero or infinite maximum gives s_t = 1).
+ *   token_scale_out  device, fp32 [M], required: receives s_t.  Feed the packed result to
+ *                    fptq_w4a4_linear with s_a = 1.0f and row_out_scale = token_scale_out, which makes
+ *                    the epilogue y = bf16(acc * s_w[o] * s_t).
+ */
+int fptq_quantize_act_dynamic(const void *x_bf16, int64_t M, int64_t K, void *xq_packed, int64_t xq_bytes,
+                              float *token_scale_out, void *stream);
+
+/*
  * The quantized linear layer proper: INT4 x INT4 matmul with INT32 accumulation and the
  * float-scale epilogue (App. J; App. B).  Picks a few-token (bandwidth-bound) kernel for small M
  * and the INT8-MFMA GEMM otherwise.

@@ -17,7 +17,7 @@ ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4:
 
 # every symbol include/fptq.h declares
 EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
-           "fptq_quantize_act_hadamard",
+           "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic",
            "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile"]
 
 _lib = None
@@ -48,6 +48,8 @@ def lib():
         L.fptq_quantize_act.argtypes = [p, i64, i64, i32, f32, p, f32, p, i64, p, p]
         L.fptq_quantize_act_hadamard.restype = i32
         L.fptq_quantize_act_hadamard.argtypes = [p, i64, i64, i32, i32, f32, p, f32, p, i64, p, p]
+        L.fptq_quantize_act_dynamic.restype = i32
+        L.fptq_quantize_act_dynamic.argtypes = [p, i64, i64, p, i64, p, p]
         for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p]
@@ -133,6 +135,17 @@ def fptq_quantize_act_hadamard(x_bf16, s_a, hadamard_block=256, scale_mode=SCALE
                                             _ptr(row_scale_in), float(s_a), _ptr(out), out.numel(), _ptr(row_scale_out),
                                             _stream()))
     return out, row_scale_out
+
+
+def fptq_quantize_act_dynamic(x_bf16, out=None, token_scale_out=None):
+    """bf16 [M, K] -> (packed uint8 blob, fp32 [M] per-token scales s_t computed at run time)."""
+    _dev(x_bf16, torch.bfloat16, "x_bf16")
+    M, K = x_bf16.shape
+    out = torch.empty(_need(M, K), dtype=torch.uint8, device=x_bf16.device) if out is None else out
+    if token_scale_out is None:
+        token_scale_out = torch.empty(M, dtype=torch.float32, device=x_bf16.device)
+    _check(lib().fptq_quantize_act_dynamic(_ptr(x_bf16), M, K, _ptr(out), out.numel(), _ptr(token_scale_out), _stream()))
+    return out, token_scale_out
 
 
 def _linear(fn, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc):

@@ -159,6 +159,28 @@ int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, 
                            row_scale_out, stream);
 }
 
+int fptq_quantize_act_dynamic(const void *x_bf16, int64_t M, int64_t K, void *xq_packed, int64_t xq_bytes,
+                              float *token_scale_out, void *stream)
+{
+    const char *fn = "fptq_quantize_act_dynamic";
+    if (!x_bf16 || !xq_packed || !token_scale_out) {
+        set_error("%s: NULL pointer", fn);
+        return FPTQ_ERR_NULL;
+    }
+    int rc = check_dims(fn, M, K, "M", "K");
+    if (rc) return rc;
+    if (xq_bytes < packed_bytes(M, K)) {
+        set_error("%s: buffer of %lld bytes, need %lld", fn, (long long)xq_bytes, (long long)packed_bytes(M, K));
+        return FPTQ_ERR_SIZE;
+    }
+    if ((rc = check_align(fn, xq_packed, 16, "xq_packed")) || (rc = check_align(fn, x_bf16, 2, "x_bf16")) ||
+        (rc = check_align(fn, token_scale_out, 4, "token_scale_out")))
+        return rc;
+    hipError_t e = launch_quantize_act_dynamic((const uint16_t *)x_bf16, M, K, (uint8_t *)xq_packed, token_scale_out,
+                                               (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
+}
+
 int fptq_quantize_act_hadamard(const void *x_bf16, int64_t M, int64_t K, int hadamard_block, int scale_mode, float eps,
                                const float *row_scale_in, float s_a, void *xq_packed, int64_t xq_bytes,
                                float *row_scale_out, void *stream)

@@ -26,6 +26,7 @@ hipError_t launch_pack_weights(const int8_t *w, int64_t N, int64_t K, uint8_t *o
 hipError_t launch_unpack(const uint8_t *packed, int64_t rows, int64_t K, int8_t *out, hipStream_t s);
 hipError_t launch_quantize_act(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
                                float inv_s_a, uint8_t *out, float *row_out, hipStream_t s);
+hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, uint8_t *out, float *s_out, hipStream_t s);
 hipError_t launch_quantize_act_hadamard(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
                                         float inv_s_a, uint8_t *out, float *row_out, hipStream_t s);
 hipError_t launch_linear_ref(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,

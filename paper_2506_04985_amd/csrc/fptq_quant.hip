@@ -176,6 +176,89 @@ __global__ __launch_bounds__(QT) void quantize_act_wave_kernel(const uint16_t *_
     }
 }
 
+// Dynamic quantization (App. B of the paper): the scale is computed at run time per token,
+// s_t = max_k |x_t,k| / 7 (NaNs ignored; a zero or infinite maximum gives s_t = 1), then
+// q = clamp(rne(x * (1 / s_t)), -8, 7).  One wave per row.  CH > 0: the row (K <= 512 * CH, K % 8 == 0)
+// stays in registers between the max reduction and the quantizer; CH == 0: any K, two passes.
+__device__ inline uint32_t abs_bits_no_nan(uint32_t h)
+{
+    uint32_t m = h & 0x7fffu;
+    return m > 0x7f80u ? 0u : m;       // bf16 magnitudes order like their bit patterns; NaN does not enter the max
+}
+
+template <int CH>
+__global__ __launch_bounds__(QT) void quantize_act_dynamic_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K,
+                                                                  uint8_t *__restrict__ out, float *__restrict__ s_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * (QT / 64) + (threadIdx.x >> 6);
+    if (t >= M) return;
+    const uint16_t *row = x + t * K;
+    const int64_t Kpad = k_tiles(K) * KT;
+
+    uint4 regs[CH > 0 ? CH : 1];
+    uint32_t mx = 0;
+    if (CH > 0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
+            regs[i] = k0 < K ? *reinterpret_cast<const uint4 *>(row + k0) : make_uint4(0, 0, 0, 0);
+            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mx = max(mx, max(abs_bits_no_nan(w[j] & 0xffffu), abs_bits_no_nan(w[j] >> 16)));
+        }
+    } else {
+        for (int64_t k = lane; k < K; k += 64) mx = max(mx, abs_bits_no_nan(row[k]));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off, 64));
+    const float amax = bf16_to_f32(mx);
+    const float s = (amax > 0.0f && mx < 0x7f80u) ? amax / 7.0f : 1.0f;
+    const float c = 1.0f / s;
+    if (lane == 0) s_out[t] = s;
+
+    if (CH > 0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
+            if (k0 < Kpad) {
+                const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+                uint32_t word = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c) << (8 * j);
+                    word |= quant_nibble(bf16_to_f32(w[j] >> 16), c) << (8 * j + 4);
+                }
+                store_word(out, M, t, k0, k0 < K ? word : 0u);
+            }
+        }
+    } else {
+        for (int64_t k0 = (int64_t)lane * QCHUNK; k0 < Kpad; k0 += 64 * QCHUNK) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int i = 0; i < QCHUNK; ++i) {
+                int64_t k = k0 + i;
+                if (k < K) word |= quant_nibble(bf16_to_f32(row[k]), c) << (4 * i);
+            }
+            store_word(out, M, t, k0, word);
+        }
+    }
+}
+
+hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, uint8_t *out, float *s_out, hipStream_t s)
+{
+    const int64_t blocks = (M + QT / 64 - 1) / (QT / 64);
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks), block(QT);
+    const bool vec = K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+    const int64_t Kpad = k_tiles(K) * KT;
+    if (vec && Kpad <= 512 * 8) quantize_act_dynamic_kernel<8><<<grid, block, 0, s>>>(x, M, K, out, s_out);
+    else if (vec && Kpad <= 512 * 16) quantize_act_dynamic_kernel<16><<<grid, block, 0, s>>>(x, M, K, out, s_out);
+    else if (vec && Kpad <= 512 * 24) quantize_act_dynamic_kernel<24><<<grid, block, 0, s>>>(x, M, K, out, s_out);
+    else quantize_act_dynamic_kernel<0><<<grid, block, 0, s>>>(x, M, K, out, s_out);
+    return hipGetLastError();
+}
+
 template <int MODE>
 static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps, const float *row_in, float inv_s_a,
                               uint8_t *out, float *row_out, hipStream_t s)
