@@ -253,6 +253,59 @@ int oracle_quantize_f32(const float *h, int64_t M, int64_t K, const float *row_s
     return 0;
 }
 
+/* Asymmetric static grid (App. D: scale and offset of every quantizer are parameters): the
+ * integer code is shifted by a zero point z before clamping, v = clamp(rne(x * c) + z, -8, 7), and
+ * represents s_a * (v - z).  NaN maps to the code of zero.  z = 0 is the symmetric quantizer. */
+static inline int8_t quantize_one_zp(float x, float c, int zp)
+{
+    float u = x * c;
+    if (u != u) return (int8_t)zp;
+    float r = rintf(u) + (float)zp;
+    if (r < -8.0f) r = -8.0f;
+    if (r > 7.0f) r = 7.0f;
+    return (int8_t)r;
+}
+
+int8_t oracle_quantize_scalar_zp(uint16_t x_bf16, float c, int zp) { return quantize_one_zp(bf16_bits_to_f32(x_bf16), c, zp); }
+
+int oracle_quantize_zp(const uint16_t *x, int64_t M, int64_t K, const float *row_scale, float s_a, int zp, int8_t *q)
+{
+    if (zp < -8 || zp > 7) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < M; ++t) {
+        float c = oracle_row_multiplier(row_scale ? row_scale[t] : 1.0f, s_a, row_scale != NULL);
+        for (int64_t k = 0; k < K; ++k) q[t * K + k] = quantize_one_zp(bf16_bits_to_f32(x[t * K + k]), c, zp);
+    }
+    return 0;
+}
+
+/* sum_k w[o, k] per output channel: what the zero point multiplies in the epilogue */
+int oracle_weight_row_sums(const int8_t *w, int64_t N, int64_t K, int32_t *sums)
+{
+    for (int64_t o = 0; o < N; ++o) {
+        int64_t s = 0;
+        for (int64_t k = 0; k < K; ++k) s += w[o * K + k];
+        sums[o] = (int32_t)s;
+    }
+    return 0;
+}
+
+/* Epilogue with the zero point removed: sum_k (v - z) w = acc - z * wsum[o], then the float scales. */
+int oracle_epilogue_zp(const int32_t *acc, int64_t M, int64_t N, float s_a, const float *s_w, const float *row_out_scale,
+                       int zp, const int32_t *w_row_sum, uint16_t *y_bf16)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < M; ++t)
+        for (int64_t o = 0; o < N; ++o) {
+            int32_t a = acc[t * N + o] - (int32_t)zp * w_row_sum[o];
+            float cw = s_a * s_w[o];
+            float yf = (float)a * cw;
+            if (row_out_scale) yf = yf * row_out_scale[t];
+            y_bf16[t * N + o] = f32_to_bf16_bits_rne(yf);
+        }
+    return 0;
+}
+
 /* App. B "Dynamic quantization": the scale factor is computed at run time for each token
  * independently, from that token's range.  With the symmetric 4-bit grid: s_t = max_k |x_t,k| / 7,
  * q = clamp(rne(x * (1 / s_t)), -8, 7).  NaNs do not enter the maximum; an all-zero (or infinite)

@@ -62,6 +62,14 @@ def lib():
         L.oracle_quantize_f32.argtypes = [p, i64, i64, p, f32, i64, p]
         L.oracle_quantize_dynamic.restype = ctypes.c_int
         L.oracle_quantize_dynamic.argtypes = [p, i64, i64, p, p]
+        L.oracle_quantize_scalar_zp.restype = ctypes.c_int8
+        L.oracle_quantize_scalar_zp.argtypes = [ctypes.c_uint16, f32, ctypes.c_int]
+        L.oracle_quantize_zp.restype = ctypes.c_int
+        L.oracle_quantize_zp.argtypes = [p, i64, i64, p, f32, ctypes.c_int, p]
+        L.oracle_weight_row_sums.restype = ctypes.c_int
+        L.oracle_weight_row_sums.argtypes = [p, i64, i64, p]
+        L.oracle_epilogue_zp.restype = ctypes.c_int
+        L.oracle_epilogue_zp.argtypes = [p, i64, i64, f32, p, p, ctypes.c_int, p, p]
         L.oracle_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -132,6 +140,36 @@ def quantize_dynamic(x_bits):
     s = np.empty(M, dtype=np.float32)
     lib().oracle_quantize_dynamic(_ptr(x_bits), M, K, _ptr(s), _ptr(q))
     return q, s
+
+
+def quantize_zp(x_bits, s_a, zero_point, row_scale=None):
+    """Asymmetric static grid (App. D): v = clamp(rne(x * S / s_a) + z, -8, 7), representing s_a (v - z)."""
+    x_bits = _c(x_bits, np.uint16)
+    M, K = x_bits.shape
+    q = np.empty((M, K), dtype=np.int8)
+    r = None if row_scale is None else _c(row_scale, np.float32)
+    if lib().oracle_quantize_zp(_ptr(x_bits), M, K, _ptr(r), float(np.float32(s_a)), int(zero_point), _ptr(q)):
+        raise ValueError("zero point outside [-8, 7]")
+    return q
+
+
+def weight_row_sums(w_int):
+    w_int = _c(w_int, np.int8)
+    N, K = w_int.shape
+    out = np.empty(N, dtype=np.int32)
+    lib().oracle_weight_row_sums(_ptr(w_int), N, K, _ptr(out))
+    return out
+
+
+def epilogue_zp(acc, s_a, s_w, zero_point, w_row_sum, row_out_scale=None):
+    """y = bf16((acc - z * wsum[o]) * (s_a * s_w[o]) [* d_t])."""
+    acc = _c(acc, np.int32)
+    M, N = acc.shape
+    s_w, ws = _c(s_w, np.float32), _c(w_row_sum, np.int32)
+    d = None if row_out_scale is None else _c(row_out_scale, np.float32)
+    y = np.empty((M, N), dtype=np.uint16)
+    lib().oracle_epilogue_zp(_ptr(acc), M, N, float(np.float32(s_a)), _ptr(s_w), _ptr(d), int(zero_point), _ptr(ws), _ptr(y))
+    return y
 
 
 def pack(v):
