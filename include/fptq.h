@@ -131,6 +131,22 @@ int fptq_quantize_act_dynamic(const void *x_bf16, int64_t M, int64_t K, void *xq
 int fptq_w4a4_linear(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
                      const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream);
 
+/*
+ * Asymmetric static activation grid (App. D: the scale and the offset of every quantizer are
+ * parameters): the integer code is shifted by a zero point z in [-8, 7] before clamping,
+ *     v = clamp(rne(x * S_t / s_a) + z, -8, 7),   representing s_a * (v - z)   (NaN -> z),
+ * and the linear layer removes it after the integer matmul:
+ *     y = bf16((acc - z * w_row_sum[o]) * (s_a * s_w[o]) [* d_t]),   w_row_sum[o] = sum_k w[o, k].
+ * fptq_weight_row_sums computes w_row_sum (device int32 [N]) offline from the unpacked int8 weights.
+ * Everything else is as in fptq_quantize_act / fptq_w4a4_linear; acc_dbg receives the raw sum_k v w.
+ */
+int fptq_quantize_act_asym(const void *x_bf16, int64_t M, int64_t K, int scale_mode, float eps, const float *row_scale_in,
+                           float s_a, int zero_point, void *xq_packed, int64_t xq_bytes, float *row_scale_out, void *stream);
+int fptq_weight_row_sums(const int8_t *w_int, int64_t N, int64_t K, int32_t *sums, void *stream);
+int fptq_w4a4_linear_zp(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                        const float *s_w, const float *row_out_scale, int zero_point, const int32_t *w_row_sum,
+                        void *y_bf16, int32_t *acc_dbg, void *stream);
+
 /* Same contract as fptq_w4a4_linear but always runs the simple one-thread-per-output kernel
  * (no MFMA, no LDS).  A second, independent GPU implementation used by the tests to cross-check
  * the tuned kernels at full size. */

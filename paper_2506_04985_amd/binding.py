@@ -17,7 +17,8 @@ ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4:
 
 # every symbol include/fptq.h declares
 EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
-           "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic",
+           "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic", "fptq_quantize_act_asym",
+           "fptq_weight_row_sums", "fptq_w4a4_linear_zp",
            "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile"]
 
 _lib = None
@@ -48,6 +49,12 @@ def lib():
         L.fptq_quantize_act.argtypes = [p, i64, i64, i32, f32, p, f32, p, i64, p, p]
         L.fptq_quantize_act_hadamard.restype = i32
         L.fptq_quantize_act_hadamard.argtypes = [p, i64, i64, i32, i32, f32, p, f32, p, i64, p, p]
+        L.fptq_quantize_act_asym.restype = i32
+        L.fptq_quantize_act_asym.argtypes = [p, i64, i64, i32, f32, p, f32, i32, p, i64, p, p]
+        L.fptq_weight_row_sums.restype = i32
+        L.fptq_weight_row_sums.argtypes = [p, i64, i64, p, p]
+        L.fptq_w4a4_linear_zp.restype = i32
+        L.fptq_w4a4_linear_zp.argtypes = [p, p, i64, i64, i64, f32, p, p, i32, p, p, p, p]
         L.fptq_quantize_act_dynamic.restype = i32
         L.fptq_quantize_act_dynamic.argtypes = [p, i64, i64, p, i64, p, p]
         for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref"):
@@ -135,6 +142,34 @@ def fptq_quantize_act_hadamard(x_bf16, s_a, hadamard_block=256, scale_mode=SCALE
                                             _ptr(row_scale_in), float(s_a), _ptr(out), out.numel(), _ptr(row_scale_out),
                                             _stream()))
     return out, row_scale_out
+
+
+def fptq_quantize_act_asym(x_bf16, s_a, zero_point, scale_mode=SCALE_NONE, eps=0.0, row_scale_in=None, out=None):
+    """bf16 [M, K] -> packed codes of the asymmetric grid v = clamp(rne(x S / s_a) + z, -8, 7)."""
+    _dev(x_bf16, torch.bfloat16, "x_bf16")
+    M, K = x_bf16.shape
+    if row_scale_in is not None:
+        _dev(row_scale_in, torch.float32, "row_scale_in")
+    out = torch.empty(_need(M, K), dtype=torch.uint8, device=x_bf16.device) if out is None else out
+    r = torch.empty(M, dtype=torch.float32, device=x_bf16.device)
+    _check(lib().fptq_quantize_act_asym(_ptr(x_bf16), M, K, scale_mode, float(eps), _ptr(row_scale_in), float(s_a),
+                                        int(zero_point), _ptr(out), out.numel(), _ptr(r), _stream()))
+    return out, r
+
+
+def fptq_weight_row_sums(w_int):
+    _dev(w_int, torch.int8, "w_int")
+    N, K = w_int.shape
+    out = torch.empty(N, dtype=torch.int32, device=w_int.device)
+    _check(lib().fptq_weight_row_sums(_ptr(w_int), N, K, _ptr(out), _stream()))
+    return out
+
+
+def fptq_w4a4_linear_zp(xq, wq, M, N, K, s_a, s_w, zero_point, w_row_sum, row_out_scale=None, out=None, want_acc=False):
+    _dev(w_row_sum, torch.int32, "w_row_sum")
+    fn = lambda a, b, m, n, k, sa, sw, d, y, acc, st: lib().fptq_w4a4_linear_zp(a, b, m, n, k, sa, sw, d, int(zero_point),
+                                                                                 _ptr(w_row_sum), y, acc, st)
+    return _linear(fn, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, None)
 
 
 def fptq_quantize_act_dynamic(x_bf16, out=None, token_scale_out=None):

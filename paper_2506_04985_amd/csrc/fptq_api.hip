@@ -48,10 +48,11 @@ static int check_align(const char *fn, const void *p, unsigned a, const char *na
 static const int64_t DECODE_MAX_M = 32;
 
 typedef hipError_t (*linear_fn)(const uint8_t *, const uint8_t *, int64_t, int64_t, int64_t, float, const float *,
-                                const float *, uint16_t *, int32_t *, hipStream_t);
+                                const float *, int, const int32_t *, uint16_t *, int32_t *, hipStream_t);
 
 static int linear_common(const char *fn, linear_fn force, const void *xq, const void *wq, int64_t M, int64_t N,
-                         int64_t K, float s_a, const float *s_w, const float *d, void *y, int32_t *acc, void *stream)
+                         int64_t K, float s_a, const float *s_w, const float *d, int zp, const int32_t *wsum, void *y,
+                         int32_t *acc, void *stream)
 {
     if (!xq || !wq || !s_w || !y) {
         set_error("%s: NULL pointer", fn);
@@ -67,10 +68,16 @@ static int linear_common(const char *fn, linear_fn force, const void *xq, const 
     }
     if ((rc = check_align(fn, xq, 16, "xq_packed")) || (rc = check_align(fn, wq, 16, "w_packed")) ||
         (rc = check_align(fn, y, 16, "y_bf16")) || (rc = check_align(fn, acc, 16, "acc_dbg")) ||
-        (rc = check_align(fn, s_w, 4, "s_w")) || (rc = check_align(fn, d, 4, "row_out_scale")))
+        (rc = check_align(fn, s_w, 4, "s_w")) || (rc = check_align(fn, d, 4, "row_out_scale")) ||
+        (rc = check_align(fn, wsum, 4, "w_row_sum")))
         return rc;
+    if (zp < -8 || zp > 7 || (zp != 0 && !wsum)) {
+        set_error("%s: zero_point must be in [-8, 7] and needs w_row_sum", fn);
+        return FPTQ_ERR_VALUE;
+    }
+    if (zp == 0) wsum = nullptr;
     linear_fn f = force ? force : (M <= DECODE_MAX_M ? launch_linear_decode : launch_linear_mfma);
-    hipError_t e = f((const uint8_t *)xq, (const uint8_t *)wq, M, N, K, s_a, s_w, d, (uint16_t *)y, acc,
+    hipError_t e = f((const uint8_t *)xq, (const uint8_t *)wq, M, N, K, s_a, s_w, d, zp, wsum, (uint16_t *)y, acc,
                      (hipStream_t)stream);
     return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
 }
@@ -109,7 +116,7 @@ int fptq_pack_weights(const int8_t *w_int, int64_t N, int64_t K, void *w_packed,
     return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_pack_weights", e);
 }
 
-static int quantize_common(const char *fn, int hadamard_block, const void *x_bf16, int64_t M, int64_t K, int scale_mode,
+static int quantize_common(const char *fn, int hadamard_block, int zero_point, const void *x_bf16, int64_t M, int64_t K, int scale_mode,
                            float eps, const float *row_scale_in, float s_a, void *xq_packed, int64_t xq_bytes,
                            float *row_scale_out, void *stream)
 {
@@ -131,8 +138,8 @@ static int quantize_common(const char *fn, int hadamard_block, const void *x_bf1
         set_error("%s: FPTQ_SCALE_GIVEN needs row_scale_in", fn);
         return FPTQ_ERR_MODE;
     }
-    if (!(s_a > 0.0f) || !std::isfinite(s_a) || !(eps >= 0.0f)) {
-        set_error("%s: s_a must be finite and > 0, eps >= 0", fn);
+    if (!(s_a > 0.0f) || !std::isfinite(s_a) || !(eps >= 0.0f) || zero_point < -8 || zero_point > 7) {
+        set_error("%s: s_a must be finite and > 0, eps >= 0, zero_point in [-8, 7]", fn);
         return FPTQ_ERR_VALUE;
     }
     if (xq_bytes < packed_bytes(M, K)) {
@@ -147,7 +154,7 @@ static int quantize_common(const char *fn, int hadamard_block, const void *x_bf1
     hipError_t e = hadamard_block
                        ? launch_quantize_act_hadamard((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv,
                                                       (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream)
-                       : launch_quantize_act((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv,
+                       : launch_quantize_act((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv, zero_point,
                                              (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream);
     return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
 }
@@ -155,8 +162,15 @@ static int quantize_common(const char *fn, int hadamard_block, const void *x_bf1
 int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, float eps, const float *row_scale_in,
                       float s_a, void *xq_packed, int64_t xq_bytes, float *row_scale_out, void *stream)
 {
-    return quantize_common("fptq_quantize_act", 0, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a, xq_packed, xq_bytes,
+    return quantize_common("fptq_quantize_act", 0, 0, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a, xq_packed, xq_bytes,
                            row_scale_out, stream);
+}
+
+int fptq_quantize_act_asym(const void *x_bf16, int64_t M, int64_t K, int scale_mode, float eps, const float *row_scale_in,
+                           float s_a, int zero_point, void *xq_packed, int64_t xq_bytes, float *row_scale_out, void *stream)
+{
+    return quantize_common("fptq_quantize_act_asym", 0, zero_point, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a, xq_packed,
+                           xq_bytes, row_scale_out, stream);
 }
 
 int fptq_quantize_act_dynamic(const void *x_bf16, int64_t M, int64_t K, void *xq_packed, int64_t xq_bytes,
@@ -189,22 +203,43 @@ int fptq_quantize_act_hadamard(const void *x_bf16, int64_t M, int64_t K, int had
         set_error("fptq_quantize_act_hadamard: hadamard_block must be 256");
         return FPTQ_ERR_SHAPE;
     }
-    return quantize_common("fptq_quantize_act_hadamard", hadamard_block, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a,
+    return quantize_common("fptq_quantize_act_hadamard", hadamard_block, 0, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a,
                            xq_packed, xq_bytes, row_scale_out, stream);
 }
 
 int fptq_w4a4_linear(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
                      const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream)
 {
-    return linear_common("fptq_w4a4_linear", nullptr, xq_packed, w_packed, M, N, K, s_a, s_w, row_out_scale, y_bf16,
-                         acc_dbg, stream);
+    return linear_common("fptq_w4a4_linear", nullptr, xq_packed, w_packed, M, N, K, s_a, s_w, row_out_scale, 0, nullptr,
+                         y_bf16, acc_dbg, stream);
+}
+
+int fptq_w4a4_linear_zp(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                        const float *s_w, const float *row_out_scale, int zero_point, const int32_t *w_row_sum,
+                        void *y_bf16, int32_t *acc_dbg, void *stream)
+{
+    return linear_common("fptq_w4a4_linear_zp", nullptr, xq_packed, w_packed, M, N, K, s_a, s_w, row_out_scale, zero_point,
+                         w_row_sum, y_bf16, acc_dbg, stream);
+}
+
+int fptq_weight_row_sums(const int8_t *w_int, int64_t N, int64_t K, int32_t *sums, void *stream)
+{
+    if (!w_int || !sums) {
+        set_error("fptq_weight_row_sums: NULL pointer");
+        return FPTQ_ERR_NULL;
+    }
+    int rc = check_dims("fptq_weight_row_sums", N, K, "N", "K");
+    if (rc) return rc;
+    if ((rc = check_align("fptq_weight_row_sums", sums, 4, "sums"))) return rc;
+    hipError_t e = launch_weight_row_sums(w_int, N, K, sums, (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_weight_row_sums", e);
 }
 
 int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
                          const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream)
 {
     return linear_common("fptq_w4a4_linear_ref", launch_linear_ref, xq_packed, w_packed, M, N, K, s_a, s_w,
-                         row_out_scale, y_bf16, acc_dbg, stream);
+                         row_out_scale, 0, nullptr, y_bf16, acc_dbg, stream);
 }
 
 int fptq_set_gemm_tile(int tile)

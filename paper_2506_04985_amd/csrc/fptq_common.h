@@ -25,16 +25,20 @@ void set_error(const char *fmt, ...);
 hipError_t launch_pack_weights(const int8_t *w, int64_t N, int64_t K, uint8_t *out, hipStream_t s);
 hipError_t launch_unpack(const uint8_t *packed, int64_t rows, int64_t K, int8_t *out, hipStream_t s);
 hipError_t launch_quantize_act(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
-                               float inv_s_a, uint8_t *out, float *row_out, hipStream_t s);
+                               float inv_s_a, int zero_point, uint8_t *out, float *row_out, hipStream_t s);
+hipError_t launch_weight_row_sums(const int8_t *w, int64_t N, int64_t K, int32_t *sums, hipStream_t s);
 hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, uint8_t *out, float *s_out, hipStream_t s);
 hipError_t launch_quantize_act_hadamard(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
                                         float inv_s_a, uint8_t *out, float *row_out, hipStream_t s);
 hipError_t launch_linear_ref(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                             const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s);
+                             const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                             hipStream_t s);
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                              const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s);
+                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                              hipStream_t s);
 hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                                const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s);
+                                const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                                hipStream_t s);
 
 void set_gemm_tile(int tile);
 
@@ -44,6 +48,12 @@ __device__ inline uint16_t bf16_rne(float f)
     uint32_t u = __float_as_uint(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
     return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// Zero-point correction of an accumulator: sum_k (v - z) w = acc - z * sum_k w (wsum == NULL: symmetric grid).
+__device__ inline int32_t remove_zero_point(int32_t acc, int zp, const int32_t *wsum, int64_t o)
+{
+    return wsum ? acc - zp * wsum[o] : acc;
 }
 
 // The dequantizing epilogue of the layer for one output: fp32 throughout, no fused operations.

@@ -84,8 +84,8 @@ __device__ inline void load_chunk(__amdgpu_buffer_rsrc_t r, uint8_t *lds_base, i
 template <class C, bool ALIGNED, bool DUMP>
 __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, int tiles_m,
-    int tiles_n, float s_a, const float *__restrict__ s_w, const float *__restrict__ d, uint16_t *__restrict__ y,
-    int32_t *__restrict__ acc_out)
+    int tiles_n, float s_a, const float *__restrict__ s_w, const float *__restrict__ d, int zp,
+    const int32_t *__restrict__ wsum, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -287,12 +287,18 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     // padded rows) so that HBM sees whole 16-byte-per-lane row segments instead of scattered quads.
     constexpr int WN = C::TN * 32;                    // channels per wave
     constexpr int PATCH_STRIDE = WN * 2 + 16;         // bytes per token row in the patch
-    constexpr int WAVE_LDS = 32 * PATCH_STRIDE + WN * 4;
+    // With an activation zero point z the sum wanted is sum_k (v - z) w = acc - z * wsum[n]; the
+    // correction is staged as 256 * z * wsum[n] next to the scales (|.| < 2^31 for K <= 65535).
+    constexpr int WAVE_LDS = 32 * PATCH_STRIDE + WN * 8;
     uint8_t *patch = lds + wave * WAVE_LDS;
     float *cwbuf = reinterpret_cast<float *>(patch + 32 * PATCH_STRIDE);
+    int32_t *zwbuf = reinterpret_cast<int32_t *>(cwbuf + WN);
     const int nw0 = n0 + wave_n * WN;
 #pragma unroll
-    for (int c = lane; c < WN; c += 64) cwbuf[c] = (s_a * s_w[min(nw0 + c, N - 1)]) * 0.00390625f;
+    for (int c = lane; c < WN; c += 64) {
+        cwbuf[c] = (s_a * s_w[min(nw0 + c, N - 1)]) * 0.00390625f;
+        if (wsum) zwbuf[c] = (zp * wsum[min(nw0 + c, N - 1)]) * 256;
+    }
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -305,8 +311,12 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const float4 c4 = *reinterpret_cast<const float4 *>(cwbuf + tn * 32 + 8 * q + 4 * fg);
-                float yf[4] = {(float)acc[tn][tm][4 * q + 0] * c4.x, (float)acc[tn][tm][4 * q + 1] * c4.y,
-                               (float)acc[tn][tm][4 * q + 2] * c4.z, (float)acc[tn][tm][4 * q + 3] * c4.w};
+                int32_t a4[4] = {acc[tn][tm][4 * q + 0], acc[tn][tm][4 * q + 1], acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]};
+                if (wsum) {
+                    const int4 z4 = *reinterpret_cast<const int4 *>(zwbuf + tn * 32 + 8 * q + 4 * fg);
+                    a4[0] -= z4.x, a4[1] -= z4.y, a4[2] -= z4.z, a4[3] -= z4.w;
+                }
+                float yf[4] = {(float)a4[0] * c4.x, (float)a4[1] * c4.y, (float)a4[2] * c4.z, (float)a4[3] * c4.w};
                 if (d) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) yf[e] = yf[e] * dm;
@@ -359,7 +369,8 @@ void set_gemm_tile(int tile) { g_forced_tile = tile; }
 
 template <class C, bool ALIGNED, bool DUMP>
 static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                              const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                              hipStream_t s)
 {
     static bool attr_set = false;
     auto kern = linear_mfma_kernel<C, ALIGNED, DUMP>;
@@ -371,28 +382,30 @@ static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     int64_t tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     if (tiles_m * tiles_n > 0x7fffffff) return hipErrorInvalidValue;
     kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(C::THREADS), C::LDS_BYTES, s>>>(
-        xq, wq, (int)M, (int)N, (int)k_tiles(K), (int)tiles_m, (int)tiles_n, s_a, s_w, d, y, acc);
+        xq, wq, (int)M, (int)N, (int)k_tiles(K), (int)tiles_m, (int)tiles_n, s_a, s_w, d, zp, wsum, y, acc);
     return hipGetLastError();
 }
 
 template <class C>
 static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                             const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+                             const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                              hipStream_t s)
 {
     const bool aligned = N % 8 == 0;
-    if (acc) return aligned ? launch_inst<C, true, true>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s)
-                            : launch_inst<C, false, true>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    return aligned ? launch_inst<C, true, false>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s)
-                   : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (acc) return aligned ? launch_inst<C, true, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
+                            : launch_inst<C, false, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    return aligned ? launch_inst<C, true, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
+                   : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                              const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                              hipStream_t s)
 {
     // Limits of this kernel: the widened accumulator is 256 * acc with |acc| <= 64 K, and one K tile
     // of all rows (rows * 64 bytes) must fit a 32-bit buffer descriptor.  Beyond them the simple
     // kernel answers.
-    if (K > 131071 || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (K > 131071 || (wsum && K > 65535) || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     // Tile shapes (all 4 waves, 4-stage ring).  The 256 x 256 tile has the best operand reuse; the
     // other two exist for shapes whose 256 x 256 tile count fills the 256 CUs badly.
     typedef GemmCfg<2, 2, 4, 4, 4> T256x256;   // waves of 128 x 128
@@ -414,10 +427,10 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     if (g_forced_tile <= 0)
         for (int i = 1; i < 4; ++i)
             if (cost[i] < cost[pick]) pick = i;
-    if (pick == 1) return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    if (pick == 2) return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (pick == 1) return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 2) return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 
 }  // namespace fptq

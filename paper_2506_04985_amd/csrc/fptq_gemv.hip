@@ -37,7 +37,8 @@ __device__ inline v4i dec_widen(int p0, int p1)
 template <int WAVES, int U, int MT, int RT>
 __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, float s_a,
-    const float *__restrict__ s_w, const float *__restrict__ d, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
+    const float *__restrict__ s_w, const float *__restrict__ d, int zp, const int32_t *__restrict__ wsum,
+    uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
 {
     __shared__ int32_t red[WAVES * RT * MT * 256];     // [WAVES][RT][MT][16 tokens][16 channels]
     const int tid = threadIdx.x, lane = tid & 63;
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
         const int t = mt * 16 + j, n = n0 + rt * 16 + i;
         if (t < M && n < N) {
             const int32_t a = sum >> 8;                // exact: the sum is 256 * acc
-            y[(int64_t)t * N + n] = dequant_bf16(a, s_a * s_w[n], d, t);
+            y[(int64_t)t * N + n] = dequant_bf16(remove_zero_point(a, zp, wsum, n), s_a * s_w[n], d, t);
             if (acc_out) acc_out[(int64_t)t * N + n] = a;
         }
     }
@@ -125,28 +126,30 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
 
 template <int WAVES, int U, int MT, int RT>
 static hipError_t launch_decode_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                                    const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+                                    const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                                    hipStream_t s)
 {
     linear_decode_kernel<WAVES, U, MT, RT><<<dim3((unsigned)((N + 16 * RT - 1) / (16 * RT))), dim3(64 * WAVES), 0, s>>>(
-        xq, wq, (int)M, (int)N, (int)k_tiles(K), s_a, s_w, d, y, acc);
+        xq, wq, (int)M, (int)N, (int)k_tiles(K), s_a, s_w, d, zp, wsum, y, acc);
     return hipGetLastError();
 }
 
 hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                                const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+                                const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                                    hipStream_t s)
 {
     // Limits: M <= 32; 256 * acc must stay in int32; the grid is one workgroup per 16 channels.
-    if (M > 32 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (M > 32 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     // K split: 16 waves per workgroup when K is long (each wave keeps at least four K tiles), so that
     // small-N / large-K matrices still put enough loads in flight on every CU; 8 otherwise.
     const bool wide = k_tiles(K) >= 64;
     if (M <= 16) {
-        if (wide) return launch_decode_cfg<16, 8, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-        return launch_decode_cfg<8, 4, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+        if (wide) return launch_decode_cfg<16, 8, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+        return launch_decode_cfg<8, 4, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     }
-    if (N >= 16384) return launch_decode_cfg<8, 4, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    if (wide) return launch_decode_cfg<16, 8, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
-    return launch_decode_cfg<8, 4, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, y, acc, s);
+    if (N >= 16384) return launch_decode_cfg<8, 4, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (wide) return launch_decode_cfg<16, 8, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    return launch_decode_cfg<8, 4, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 
 }  // namespace fptq

@@ -45,8 +45,9 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
 // instruction; one thread per output.  Also the library's answer for shapes nothing else covers.
 __global__ __launch_bounds__(256) void linear_ref_kernel(const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq,
                                                          int64_t M, int64_t N, int64_t ktiles, float s_a,
-                                                         const float *__restrict__ s_w, const float *__restrict__ d,
-                                                         uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
+                                                         const float *__restrict__ s_w, const float *__restrict__ d, int zp,
+                                                         const int32_t *__restrict__ wsum, uint16_t *__restrict__ y,
+                                                         int32_t *__restrict__ acc_out)
 {
     const int64_t blocks_n = (N + 15) / 16;
     int64_t o = ((int64_t)blockIdx.x % blocks_n) * 16 + (threadIdx.x & 15);
@@ -66,8 +67,8 @@ __global__ __launch_bounds__(256) void linear_ref_kernel(const uint8_t *__restri
         }
     }
     float cw = s_a * s_w[o];
-    y[t * N + o] = dequant_bf16(acc, cw, d, t);
-    if (acc_out) acc_out[t * N + o] = acc;
+    y[t * N + o] = dequant_bf16(remove_zero_point(acc, zp, wsum, o), cw, d, t);
+    if (acc_out) acc_out[t * N + o] = acc;          // the raw accumulator sum_k v w
 }
 
 hipError_t launch_pack_weights(const int8_t *w, int64_t N, int64_t K, uint8_t *out, hipStream_t s)
@@ -87,12 +88,35 @@ hipError_t launch_unpack(const uint8_t *packed, int64_t rows, int64_t K, int8_t 
     return hipGetLastError();
 }
 
+// sum_k w[o][k] per output channel (what an activation zero point multiplies); one wave per row
+__global__ __launch_bounds__(256) void weight_row_sums_kernel(const int8_t *__restrict__ w, int64_t N, int64_t K,
+                                                              int32_t *__restrict__ sums)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t o = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (o >= N) return;
+    int s = 0;
+    for (int64_t k = lane; k < K; k += 64) s += w[o * K + k];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) sums[o] = s;
+}
+
+hipError_t launch_weight_row_sums(const int8_t *w, int64_t N, int64_t K, int32_t *sums, hipStream_t s)
+{
+    int64_t blocks = (N + 3) / 4;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    weight_row_sums_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(w, N, K, sums);
+    return hipGetLastError();
+}
+
 hipError_t launch_linear_ref(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                             const float *s_w, const float *d, uint16_t *y, int32_t *acc, hipStream_t s)
+                             const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                             hipStream_t s)
 {
     int64_t blocks = ((N + 15) / 16) * ((M + 15) / 16);
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    linear_ref_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(xq, wq, M, N, k_tiles(K), s_a, s_w, d, y, acc);
+    linear_ref_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(xq, wq, M, N, k_tiles(K), s_a, s_w, d, zp, wsum, y, acc);
     return hipGetLastError();
 }
 

@@ -15,13 +15,14 @@ constexpr int QREG_CHUNKS = 16; // chunks a thread keeps in registers: rows up t
 
 __device__ inline float bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
 
-// q = clamp(rne(x * c), -8, 7) as a 4-bit two's complement field; NaN -> 0
-__device__ inline uint32_t quant_nibble(float x, float c)
+// q = clamp(rne(x * c) + z, -8, 7) as a 4-bit two's complement field; NaN -> z (the code of zero).
+// z = 0 is the symmetric grid; adding 0.0f changes nothing, so one routine serves both.
+__device__ inline uint32_t quant_nibble(float x, float c, float zpf = 0.0f)
 {
     float u = x * c;
-    float r = __builtin_rintf(u);
+    float r = __builtin_rintf(u) + zpf;
     r = fminf(fmaxf(r, -8.0f), 7.0f);
-    int q = (u != u) ? 0 : (int)r;
+    int q = (u != u) ? (int)zpf : (int)r;
     return (uint32_t)q & 15u;
 }
 
@@ -46,7 +47,7 @@ __device__ inline void store_word(uint8_t *out, int64_t M, int64_t t, int64_t k0
 // VEC: K is a multiple of 8, so every row starts 16-byte aligned and chunks never straddle K.
 template <int MODE, bool VEC>
 __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K, float eps,
-                                                          const float *__restrict__ row_in, float inv_s_a,
+                                                          const float *__restrict__ row_in, float inv_s_a, float zpf,
                                                           uint8_t *__restrict__ out, float *__restrict__ row_out)
 {
     __shared__ double red[QT / 64];
@@ -102,8 +103,8 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
                 uint32_t word = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c) << (8 * j);
-                    word |= quant_nibble(bf16_to_f32(w[j] >> 16), c) << (8 * j + 4);
+                    word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c, zpf) << (8 * j);
+                    word |= quant_nibble(bf16_to_f32(w[j] >> 16), c, zpf) << (8 * j + 4);
                 }
                 store_word(out, M, t, k0, k0 < K ? word : 0u);
             }
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
 #pragma unroll
             for (int i = 0; i < QCHUNK; ++i) {
                 int64_t k = k0 + i;
-                if (k < K) word |= quant_nibble(bf16_to_f32(row[k]), c) << (4 * i);   // K padding stays zero
+                if (k < K) word |= quant_nibble(bf16_to_f32(row[k]), c, zpf) << (4 * i);   // K padding stays zero
             }
             store_word(out, M, t, k0, word);
         }
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
 // One wave per row, CH 16-byte chunks per lane (K <= 512 * CH, K % 8 == 0, 16-byte aligned rows).
 template <int MODE, int CH>
 __global__ __launch_bounds__(QT) void quantize_act_wave_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K, float eps,
-                                                               const float *__restrict__ row_in, float inv_s_a,
+                                                               const float *__restrict__ row_in, float inv_s_a, float zpf,
                                                                uint8_t *__restrict__ out, float *__restrict__ row_out)
 {
     const int lane = threadIdx.x & 63;
@@ -168,8 +169,8 @@ __global__ __launch_bounds__(QT) void quantize_act_wave_kernel(const uint16_t *_
             uint32_t word = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c) << (8 * j);
-                word |= quant_nibble(bf16_to_f32(w[j] >> 16), c) << (8 * j + 4);
+                word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c, zpf) << (8 * j);
+                word |= quant_nibble(bf16_to_f32(w[j] >> 16), c, zpf) << (8 * j + 4);
             }
             store_word(out, M, t, k0, k0 < K ? word : 0u);     // K padding stays zero
         }
@@ -261,7 +262,7 @@ hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, 
 
 template <int MODE>
 static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps, const float *row_in, float inv_s_a,
-                              uint8_t *out, float *row_out, hipStream_t s)
+                              float zpf, uint8_t *out, float *row_out, hipStream_t s)
 {
     dim3 grid((unsigned)M), block(QT);
     const bool vec = K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
@@ -269,28 +270,28 @@ static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps
     if (vec && Kpad <= 512 * 24) {
         dim3 wgrid((unsigned)((M + QT / 64 - 1) / (QT / 64)));
         if (Kpad <= 512 * 8)
-            quantize_act_wave_kernel<MODE, 8><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+            quantize_act_wave_kernel<MODE, 8><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
         else if (Kpad <= 512 * 16)
-            quantize_act_wave_kernel<MODE, 16><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+            quantize_act_wave_kernel<MODE, 16><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
         else
-            quantize_act_wave_kernel<MODE, 24><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+            quantize_act_wave_kernel<MODE, 24><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
         return hipGetLastError();
     }
     if (vec)
-        quantize_act_kernel<MODE, true><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+        quantize_act_kernel<MODE, true><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
     else
-        quantize_act_kernel<MODE, false><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, out, row_out);
+        quantize_act_kernel<MODE, false><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize_act(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
-                               float inv_s_a, uint8_t *out, float *row_out, hipStream_t s)
+                               float inv_s_a, int zero_point, uint8_t *out, float *row_out, hipStream_t s)
 {
     if (M > 0x7fffffff) return hipErrorInvalidValue;
     switch (mode) {
-    case FPTQ_SCALE_NONE: return launch_mode<FPTQ_SCALE_NONE>(x, M, K, eps, row_in, inv_s_a, out, row_out, s);
-    case FPTQ_SCALE_RMS: return launch_mode<FPTQ_SCALE_RMS>(x, M, K, eps, row_in, inv_s_a, out, row_out, s);
-    default: return launch_mode<FPTQ_SCALE_GIVEN>(x, M, K, eps, row_in, inv_s_a, out, row_out, s);
+    case FPTQ_SCALE_NONE: return launch_mode<FPTQ_SCALE_NONE>(x, M, K, eps, row_in, inv_s_a, (float)zero_point, out, row_out, s);
+    case FPTQ_SCALE_RMS: return launch_mode<FPTQ_SCALE_RMS>(x, M, K, eps, row_in, inv_s_a, (float)zero_point, out, row_out, s);
+    default: return launch_mode<FPTQ_SCALE_GIVEN>(x, M, K, eps, row_in, inv_s_a, (float)zero_point, out, row_out, s);
     }
 }
 
