@@ -306,6 +306,35 @@ int oracle_epilogue_zp(const int32_t *acc, int64_t M, int64_t N, float s_a, cons
     return 0;
 }
 
+/* Sec. 3.1.3, Eq. (5)-(7): one step of the scaled residual stream, fused with the quantizer of
+ * the next block's input.  Given the scaled residual X~_{n-1}, the scaled block output Y~_{n-1}
+ * and S_{n-1}:  Z~ = X~ + Y~,  nrm = RMS(Z~),  S_n = S_{n-1} / nrm,  X~_n = Z~ / nrm (unit RMS:
+ * at once the new residual and the gain-free RMSNorm output), q = quantizer(X~_n / s_a).
+ * fp32 recipe: z = (float)x + (float)y; sum of z^2 in fp64; inv = (float)(1 / sqrt(ss / K + eps));
+ * S_n = S_{n-1} * inv; X~_n = bf16(z * inv); c = inv * (1.0f / s_a); q = clamp(rne(z * c), -8, 7). */
+int oracle_residual_norm_quantize(const uint16_t *x_res, const uint16_t *y_blk, int64_t M, int64_t K, const float *s_prev,
+                                  float eps, float s_a, uint16_t *x_next, float *s_next, int8_t *q)
+{
+    float inv_sa = 1.0f / s_a;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < M; ++t) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            float z = bf16_bits_to_f32(x_res[t * K + k]) + bf16_bits_to_f32(y_blk[t * K + k]);
+            ss += (double)z * (double)z;
+        }
+        float inv = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
+        s_next[t] = (s_prev ? s_prev[t] : 1.0f) * inv;
+        float c = inv * inv_sa;
+        for (int64_t k = 0; k < K; ++k) {
+            float z = bf16_bits_to_f32(x_res[t * K + k]) + bf16_bits_to_f32(y_blk[t * K + k]);
+            x_next[t * K + k] = f32_to_bf16_bits_rne(z * inv);
+            q[t * K + k] = quantize_one(z, c);
+        }
+    }
+    return 0;
+}
+
 /* App. B "Dynamic quantization": the scale factor is computed at run time for each token
  * independently, from that token's range.  With the symmetric 4-bit grid: s_t = max_k |x_t,k| / 7,
  * q = clamp(rne(x * (1 / s_t)), -8, 7).  NaNs do not enter the maximum; an all-zero (or infinite)

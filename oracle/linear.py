@@ -70,6 +70,8 @@ def lib():
         L.oracle_weight_row_sums.argtypes = [p, i64, i64, p]
         L.oracle_epilogue_zp.restype = ctypes.c_int
         L.oracle_epilogue_zp.argtypes = [p, i64, i64, f32, p, p, ctypes.c_int, p, p]
+        L.oracle_residual_norm_quantize.restype = ctypes.c_int
+        L.oracle_residual_norm_quantize.argtypes = [p, p, i64, i64, p, f32, f32, p, p, p]
         L.oracle_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -170,6 +172,20 @@ def epilogue_zp(acc, s_a, s_w, zero_point, w_row_sum, row_out_scale=None):
     y = np.empty((M, N), dtype=np.uint16)
     lib().oracle_epilogue_zp(_ptr(acc), M, N, float(np.float32(s_a)), _ptr(s_w), _ptr(d), int(zero_point), _ptr(ws), _ptr(y))
     return y
+
+
+def residual_norm_quantize(x_res_bits, y_bits, s_a, s_prev=None, eps=0.0):
+    """Sec. 3.1.3 Eq. (5)-(7): Z~ = X~ + Y~, S_n = S_{n-1} / RMS(Z~), X~_n = Z~ / RMS(Z~), q = quantize(X~_n / s_a).
+    Returns dict(x_next (bf16 bits), s_next (fp32 [M]), q (int8 [M, K]))."""
+    x_res_bits, y_bits = _c(x_res_bits, np.uint16), _c(y_bits, np.uint16)
+    M, K = x_res_bits.shape
+    sp = None if s_prev is None else _c(s_prev, np.float32)
+    x_next = np.empty((M, K), np.uint16)
+    s_next = np.empty(M, np.float32)
+    q = np.empty((M, K), np.int8)
+    lib().oracle_residual_norm_quantize(_ptr(x_res_bits), _ptr(y_bits), M, K, _ptr(sp), float(eps), float(np.float32(s_a)),
+                                        _ptr(x_next), _ptr(s_next), _ptr(q))
+    return {"x_next": x_next, "s_next": s_next, "q": q}
 
 
 def pack(v):
