@@ -102,6 +102,25 @@ int fptq_quantize_act_hadamard(const void *x_bf16, int64_t M, int64_t K, int had
                                float *row_scale_out, void *stream);
 
 /*
+ * One step of the scaled residual stream (Sec. 3.1.3, Eq. 5-7) fused with the quantizer of the next
+ * block's input, in one pass over the two inputs:
+ *     Z~ = X~_{n-1} + Y~_{n-1};  nrm = sqrt(mean_k Z~^2 + eps);  S_n = S_{n-1} / nrm;
+ *     X~_n = Z~ / nrm  (new residual and, at once, the gain-free RMSNorm output);
+ *     q = clamp(rne(X~_n / s_a), -8, 7), packed.
+ *   x_res_bf16, y_bf16  device, bf16 [M x K]: the scaled residual and the scaled block output
+ *   s_prev              device, fp32 [M] or NULL (= all ones, the first block)
+ *   x_next_bf16         device, bf16 [M x K]: receives X~_n (may alias x_res_bf16 or y_bf16)
+ *   s_next              device, fp32 [M]: receives S_n
+ *   xq_packed           device, packed INT4 of X~_n / s_a for fptq_w4a4_linear
+ * Arithmetic (fp32 unless noted): z = (float)x + (float)y; sum of z^2 in fp64;
+ * inv = (float)(1 / sqrt(ss / K + eps)); S_n = S_{n-1} * inv; X~_n = bf16(z * inv);
+ * c = inv * (1.0f / s_a); q = clamp(rne(z * c), -8, 7).
+ */
+int fptq_residual_norm_quantize(const void *x_res_bf16, const void *y_bf16, int64_t M, int64_t K, const float *s_prev,
+                                float eps, float s_a, void *x_next_bf16, float *s_next, void *xq_packed, int64_t xq_bytes,
+                                void *stream);
+
+/*
  * Dynamic activation quantization (App. B "Dynamic quantization"; the paper's second run-time
  * setting, App. J "Dynamic INT4 runtime"): the scale is computed per token at run time,
  *     s_t = max_k |x_t,k| / 7,   q = clamp(rne(x * (1 / s_t)), -8, 7)    (fp32; NaNs ignored in the

@@ -18,7 +18,7 @@ ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4:
 # every symbol include/fptq.h declares
 EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
            "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic", "fptq_quantize_act_asym",
-           "fptq_weight_row_sums", "fptq_w4a4_linear_zp",
+           "fptq_weight_row_sums", "fptq_w4a4_linear_zp", "fptq_residual_norm_quantize",
            "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile"]
 
 _lib = None
@@ -55,6 +55,8 @@ def lib():
         L.fptq_weight_row_sums.argtypes = [p, i64, i64, p, p]
         L.fptq_w4a4_linear_zp.restype = i32
         L.fptq_w4a4_linear_zp.argtypes = [p, p, i64, i64, i64, f32, p, p, i32, p, p, p, p]
+        L.fptq_residual_norm_quantize.restype = i32
+        L.fptq_residual_norm_quantize.argtypes = [p, p, i64, i64, p, f32, f32, p, p, p, i64, p]
         L.fptq_quantize_act_dynamic.restype = i32
         L.fptq_quantize_act_dynamic.argtypes = [p, i64, i64, p, i64, p, p]
         for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref"):
@@ -170,6 +172,21 @@ def fptq_w4a4_linear_zp(xq, wq, M, N, K, s_a, s_w, zero_point, w_row_sum, row_ou
     fn = lambda a, b, m, n, k, sa, sw, d, y, acc, st: lib().fptq_w4a4_linear_zp(a, b, m, n, k, sa, sw, d, int(zero_point),
                                                                                  _ptr(w_row_sum), y, acc, st)
     return _linear(fn, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, None)
+
+
+def fptq_residual_norm_quantize(x_res, y_blk, s_a, s_prev=None, eps=0.0, x_next=None, s_next=None, out=None):
+    """Residual add + norm + S_n update + quantizer in one pass: returns (X~_n bf16, S_n fp32 [M], packed uint8)."""
+    _dev(x_res, torch.bfloat16, "x_res")
+    _dev(y_blk, torch.bfloat16, "y_blk")
+    M, K = x_res.shape
+    if s_prev is not None:
+        _dev(s_prev, torch.float32, "s_prev")
+    x_next = torch.empty_like(x_res) if x_next is None else x_next
+    s_next = torch.empty(M, dtype=torch.float32, device=x_res.device) if s_next is None else s_next
+    out = torch.empty(_need(M, K), dtype=torch.uint8, device=x_res.device) if out is None else out
+    _check(lib().fptq_residual_norm_quantize(_ptr(x_res), _ptr(y_blk), M, K, _ptr(s_prev), float(eps), float(s_a),
+                                             _ptr(x_next), _ptr(s_next), _ptr(out), out.numel(), _stream()))
+    return x_next, s_next, out
 
 
 def fptq_quantize_act_dynamic(x_bf16, out=None, token_scale_out=None):

@@ -173,6 +173,35 @@ int fptq_quantize_act_asym(const void *x_bf16, int64_t M, int64_t K, int scale_m
                            xq_bytes, row_scale_out, stream);
 }
 
+int fptq_residual_norm_quantize(const void *x_res_bf16, const void *y_bf16, int64_t M, int64_t K, const float *s_prev,
+                                float eps, float s_a, void *x_next_bf16, float *s_next, void *xq_packed, int64_t xq_bytes,
+                                void *stream)
+{
+    const char *fn = "fptq_residual_norm_quantize";
+    if (!x_res_bf16 || !y_bf16 || !x_next_bf16 || !s_next || !xq_packed) {
+        set_error("%s: NULL pointer", fn);
+        return FPTQ_ERR_NULL;
+    }
+    int rc = check_dims(fn, M, K, "M", "K");
+    if (rc) return rc;
+    if (!(s_a > 0.0f) || !std::isfinite(s_a) || !(eps >= 0.0f)) {
+        set_error("%s: s_a must be finite and > 0, eps >= 0", fn);
+        return FPTQ_ERR_VALUE;
+    }
+    if (xq_bytes < packed_bytes(M, K)) {
+        set_error("%s: buffer of %lld bytes, need %lld", fn, (long long)xq_bytes, (long long)packed_bytes(M, K));
+        return FPTQ_ERR_SIZE;
+    }
+    if ((rc = check_align(fn, xq_packed, 16, "xq_packed")) || (rc = check_align(fn, x_res_bf16, 2, "x_res_bf16")) ||
+        (rc = check_align(fn, y_bf16, 2, "y_bf16")) || (rc = check_align(fn, x_next_bf16, 2, "x_next_bf16")) ||
+        (rc = check_align(fn, s_prev, 4, "s_prev")) || (rc = check_align(fn, s_next, 4, "s_next")))
+        return rc;
+    volatile float inv = 1.0f / s_a;
+    hipError_t e = launch_residual_norm_quantize((const uint16_t *)x_res_bf16, (const uint16_t *)y_bf16, M, K, s_prev, eps, inv,
+                                                 (uint16_t *)x_next_bf16, s_next, (uint8_t *)xq_packed, (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
+}
+
 int fptq_quantize_act_dynamic(const void *x_bf16, int64_t M, int64_t K, void *xq_packed, int64_t xq_bytes,
                               float *token_scale_out, void *stream)
 {

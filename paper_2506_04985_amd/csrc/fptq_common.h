@@ -26,6 +26,8 @@ hipError_t launch_pack_weights(const int8_t *w, int64_t N, int64_t K, uint8_t *o
 hipError_t launch_unpack(const uint8_t *packed, int64_t rows, int64_t K, int8_t *out, hipStream_t s);
 hipError_t launch_quantize_act(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
                                float inv_s_a, int zero_point, uint8_t *out, float *row_out, hipStream_t s);
+hipError_t launch_residual_norm_quantize(const uint16_t *xr, const uint16_t *yb, int64_t M, int64_t K, const float *s_prev,
+                                         float eps, float inv_s_a, uint16_t *x_next, float *s_next, uint8_t *out, hipStream_t s);
 hipError_t launch_weight_row_sums(const int8_t *w, int64_t N, int64_t K, int32_t *sums, hipStream_t s);
 hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, uint8_t *out, float *s_out, hipStream_t s);
 hipError_t launch_quantize_act_hadamard(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,

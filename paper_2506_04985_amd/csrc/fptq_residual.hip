@@ -1,0 +1,131 @@
+// One step of the scaled residual stream of Sec. 3.1.3 (Eq. 5-7 of the paper), fused with the
+// quantizer of the next block's input: Z~ = X~ + Y~, nrm = RMS(Z~), S_n = S_{n-1} / nrm,
+// X~_n = Z~ / nrm (new residual = gain-free RMSNorm output), q = clamp(rne(X~_n / s_a), -8, 7),
+// packed.  One pass: both inputs are read once, the sum stays in registers as fp32 between the
+// fp64 reduction and the two outputs.  Bound: HBM, 4 bytes read and 2.5 bytes written per value.
+//
+// fp32 recipe: z = (float)x + (float)y; inv = (float)(1 / sqrt(sum z^2 / K + eps)) with the sum in
+// fp64; S_n = S_{n-1} * inv; X~_n = bf16(z * inv); c = inv * (1.0f / s_a); q = clamp(rne(z * c)).
+#include "fptq_common.h"
+
+namespace fptq {
+
+__device__ inline float r_bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
+
+__device__ inline uint32_t r_quant_nibble(float z, float c)
+{
+    float u = z * c;
+    float r = __builtin_rintf(u);
+    r = fminf(fmaxf(r, -8.0f), 7.0f);
+    int q = (u != u) ? 0 : (int)r;
+    return (uint32_t)q & 15u;
+}
+
+typedef __bf16 r_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float r_float2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t r_pack_bf16(float lo, float hi)
+{
+    r_float2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, r_bf16x2));
+}
+
+// One wave per row.  CH > 0: K % 8 == 0, K <= 512 * CH, rows 16-byte aligned, z kept in registers.
+// CH == 0: any K, the inputs are read twice (the second time from cache).
+template <int CH>
+__global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint16_t *__restrict__ xr, const uint16_t *__restrict__ yb,
+                                                                     int64_t M, int64_t K, const float *__restrict__ s_prev,
+                                                                     float eps, float inv_s_a, uint16_t *__restrict__ x_next,
+                                                                     float *__restrict__ s_next, uint8_t *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= M) return;
+    const uint16_t *xrow = xr + t * K, *yrow = yb + t * K;
+    uint16_t *orow = x_next + t * K;
+    const int64_t Kpad = k_tiles(K) * KT;
+
+    float z[CH > 0 ? CH : 1][8];
+    double ss = 0.0;
+    if (CH > 0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int64_t k0 = ((int64_t)i * 64 + lane) * 8;
+            uint4 a = make_uint4(0, 0, 0, 0), b = a;
+            if (k0 < K) {
+                a = *reinterpret_cast<const uint4 *>(xrow + k0);
+                b = *reinterpret_cast<const uint4 *>(yrow + k0);
+            }
+            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                z[i][2 * j] = r_bf16_to_f32(aw[j] & 0xffffu) + r_bf16_to_f32(bw[j] & 0xffffu);
+                z[i][2 * j + 1] = r_bf16_to_f32(aw[j] >> 16) + r_bf16_to_f32(bw[j] >> 16);
+                ss += (double)z[i][2 * j] * (double)z[i][2 * j];
+                ss += (double)z[i][2 * j + 1] * (double)z[i][2 * j + 1];
+            }
+        }
+    } else {
+        for (int64_t k = lane; k < K; k += 64) {
+            const float v = r_bf16_to_f32(xrow[k]) + r_bf16_to_f32(yrow[k]);
+            ss += (double)v * (double)v;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    const float inv = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
+    if (lane == 0) s_next[t] = (s_prev ? s_prev[t] : 1.0f) * inv;
+    const float c = inv * inv_s_a;
+
+    if (CH > 0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int64_t k0 = ((int64_t)i * 64 + lane) * 8;
+            if (k0 < K) {
+                uint32_t word = 0, o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    o[j] = r_pack_bf16(z[i][2 * j] * inv, z[i][2 * j + 1] * inv);
+                    word |= r_quant_nibble(z[i][2 * j], c) << (8 * j);
+                    word |= r_quant_nibble(z[i][2 * j + 1], c) << (8 * j + 4);
+                }
+                *reinterpret_cast<uint4 *>(orow + k0) = make_uint4(o[0], o[1], o[2], o[3]);
+                *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = word;
+            } else if (k0 < Kpad) {
+                *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = 0u;   // K padding
+            }
+        }
+    } else {
+        for (int64_t k0 = (int64_t)lane * 8; k0 < Kpad; k0 += 512) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int64_t k = k0 + e;
+                if (k < K) {
+                    const float v = r_bf16_to_f32(xrow[k]) + r_bf16_to_f32(yrow[k]);
+                    orow[k] = (uint16_t)(r_pack_bf16(v * inv, 0.0f) & 0xffffu);
+                    word |= r_quant_nibble(v, c) << (4 * e);
+                }
+            }
+            *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = word;
+        }
+    }
+}
+
+hipError_t launch_residual_norm_quantize(const uint16_t *xr, const uint16_t *yb, int64_t M, int64_t K, const float *s_prev,
+                                         float eps, float inv_s_a, uint16_t *x_next, float *s_next, uint8_t *out, hipStream_t s)
+{
+    const int64_t blocks = (M + 3) / 4;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks), block(256);
+    const bool vec = K % 8 == 0 && ((reinterpret_cast<uintptr_t>(xr) | reinterpret_cast<uintptr_t>(yb) |
+                                     reinterpret_cast<uintptr_t>(x_next)) & 15) == 0;
+    if (vec && K <= 512 * 8)
+        residual_norm_quantize_kernel<8><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
+    else if (vec && K <= 512 * 16)
+        residual_norm_quantize_kernel<16><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
+    else
+        residual_norm_quantize_kernel<0><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
+    return hipGetLastError();
+}
+
+}  // namespace fptq
