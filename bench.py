@@ -151,6 +151,9 @@ def main():
            "gemm_only_dense_int4_activations_tops": round(dense_tops, 1),
            "roofline": roofline}
 
+    # ------------------------------------------------------------------ activation-side kernels and the widened rows
+    out["activation_kernels"] = activation_summary(torch, fptq, dev, x_gu, x_dn, r_dn, s_gu, s_dn, gate, down, layers, xq_dn, ys)
+
     # ------------------------------------------------------------------ decode summary (config c4)
     if not args.no_decode:
         out["decode"] = decode_summary(torch, fptq, dev)
@@ -170,6 +173,57 @@ def main():
                                "sample": "the full c2 step once (2048 tokens, three linears, quantizer included; weight "
                                          "generation excluded)"}
     print(json.dumps(out))
+
+
+def graph_time_us(torch, fn, iters=20, replays=5):
+    """Average time of one call of fn, launch overhead removed by replaying a captured graph."""
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(g, stream=st):
+        for _ in range(iters):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (iters * replays)
+
+
+def activation_summary(torch, fptq, dev, x_gu, x_dn, r_dn, s_gu, s_dn, gate, down, layers, xq_dn, ys):
+    """GB/s of the bandwidth-bound activation kernels on the c2 tensors (algorithmic bytes / time), and the
+    down projection through the zero-point epilogue."""
+    M = gate.M
+    res = {}
+
+    def entry(name, us, nbytes):
+        res[name] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "pct_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS * 100, 1)}
+
+    xq_a = torch.empty(fptq.fptq_packed_bytes(M, gate.K), dtype=torch.uint8, device=dev)
+    xq_b = torch.empty(fptq.fptq_packed_bytes(M, down.K), dtype=torch.uint8, device=dev)
+    r_out = torch.empty(M, dtype=torch.float32, device=dev)
+    b_a = M * gate.K * 2.5 + 4 * M
+    b_b = M * down.K * 2.5 + 8 * M
+    entry("quantize_rms_2048x4096", graph_time_us(torch, lambda: fptq.fptq_quantize_act(x_gu, s_gu, gate.mode, gate.eps, None, out=xq_a, row_scale_out=r_out)), b_a)
+    entry("quantize_given_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act(x_dn, s_dn, down.mode, down.eps, r_dn, out=xq_b, row_scale_out=r_out)), b_b)
+    entry("hadamard256_quantize_given_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act_hadamard(x_dn, s_dn, 256, down.mode, down.eps, r_dn, out=xq_b, row_scale_out=r_out)), b_b)
+    entry("dynamic_quantize_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act_dynamic(x_dn, out=xq_b, token_scale_out=r_out)), b_b)
+    x_next = torch.empty_like(x_gu)
+    y_blk = (torch.randn(x_gu.shape, device=dev) * 0.5).to(torch.bfloat16)
+    entry("residual_norm_quantize_2048x4096", graph_time_us(torch, lambda: fptq.fptq_residual_norm_quantize(x_gu, y_blk, s_gu, None, gate.eps, x_next=x_next, s_next=r_out, out=xq_a)), M * gate.K * 6.5 + 4 * M)
+    case, wq, s_w = layers[2]
+    wsum = torch.zeros(case.N, dtype=torch.int32, device=dev)
+    us = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear_zp(xq_dn, wq, M, case.N, case.K, s_dn, s_w, 3, wsum, out=ys[2]))
+    res["down_linear_zero_point_epilogue"] = {"us": round(us, 2), "TOPS": round(case.ops / us / 1e6, 1)}
+    us = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq_dn, wq, M, case.N, case.K, s_dn, s_w, out=ys[2]))
+    res["down_linear_symmetric"] = {"us": round(us, 2), "TOPS": round(case.ops / us / 1e6, 1)}
+    return res
 
 
 def decode_summary(torch, fptq, dev):
