@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode summary")
+    ap.add_argument("--shapes-out", default=None,
+                    help="also time every prefill linear of configs c2, c3, c5 (their own synthetic activations and "
+                         "uniform random INT4 activations) and write the table to this JSON file")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one elementwise kernel that reads 1 GiB and writes 1 GiB: under rocprofv3 --pmc "
                          "its FETCH_SIZE / WRITE_SIZE readings give the counter scale for a known byte count")
@@ -77,46 +80,57 @@ def main():
     M = gate.M
     x_gu, x_dn = dev_bf16(in_gu.x_bits), dev_bf16(in_dn.x_bits)
     r_dn = torch.from_numpy(in_dn.row_scale_in).to(dev)
+    # gate and up read the same quantized X, so their weights are concatenated along N when they are packed
+    # (offline, like every other weight preparation) and one launch computes both: Y[:, :11008] is the gate
+    # output, Y[:, 11008:] the up output.
     layers = []
-    for case in (gate, up, down):
-        w, s_w = synth.draw_weights(case)
-        layers.append((case, fptq.fptq_pack_weights(torch.from_numpy(w).to(dev)), torch.from_numpy(s_w).to(dev)))
-        del w
+    w_g, s_g = synth.draw_weights(gate)
+    w_u, s_u = synth.draw_weights(up)
+    w_gu = torch.from_numpy(np.concatenate([w_g, w_u], axis=0)).to(dev)
+    layers.append(("gate_up", gate.N + up.N, gate.K, fptq.fptq_pack_weights(w_gu), torch.from_numpy(np.concatenate([s_g, s_u])).to(dev)))
+    separate = [(c, fptq.fptq_pack_weights(torch.from_numpy(w).to(dev)), torch.from_numpy(sw).to(dev)) for c, w, sw in ((gate, w_g, s_g), (up, w_u, s_u))]
+    del w_g, w_u, w_gu
+    w_d, s_d = synth.draw_weights(down)
+    layers.append(("down", down.N, down.K, fptq.fptq_pack_weights(torch.from_numpy(w_d).to(dev)), torch.from_numpy(s_d).to(dev)))
+    del w_d
     xq_gu = torch.empty(fptq.fptq_packed_bytes(M, gate.K), dtype=torch.uint8, device=dev)
     xq_dn = torch.empty(fptq.fptq_packed_bytes(M, down.K), dtype=torch.uint8, device=dev)
     r_out = torch.empty(M, dtype=torch.float32, device=dev)
-    ys = [torch.empty((M, c.N), dtype=torch.bfloat16, device=dev) for c, _, _ in layers]
+    ys = [torch.empty((M, n), dtype=torch.bfloat16, device=dev) for _, n, _, _, _ in layers]
     s_gu, s_dn = float(in_gu.s_a), float(in_dn.s_a)
     gemm_events = []
 
-    def step(record=False):
-        fptq.fptq_quantize_act(x_gu, s_gu, gate.mode, gate.eps, None, out=xq_gu, row_scale_out=r_out)
-        for i, (case, wq, s_w) in enumerate(layers):
-            if i == 2:
+    def step(record=-1):
+        """One pass of the hot path; record = index of the GEMM to bracket with events (-1: none).  Only one
+        GEMM per step is bracketed because each event pair costs about 4 us of stream time."""
+        for i, (name, n, k, wq, s_w) in enumerate(layers):
+            if i == 0:
+                fptq.fptq_quantize_act(x_gu, s_gu, gate.mode, gate.eps, None, out=xq_gu, row_scale_out=r_out)
+            else:
                 fptq.fptq_quantize_act(x_dn, s_dn, down.mode, down.eps, r_dn, out=xq_dn, row_scale_out=r_out)
-            xq, s_a = (xq_gu, s_gu) if i < 2 else (xq_dn, s_dn)
-            if record:
+            xq, s_a = (xq_gu, s_gu) if i == 0 else (xq_dn, s_dn)
+            if record == i:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-            fptq.fptq_w4a4_linear(xq, wq, M, case.N, case.K, s_a, s_w, out=ys[i])
-            if record:
+            fptq.fptq_w4a4_linear(xq, wq, M, n, k, s_a, s_w, out=ys[i])
+            if record == i:
                 e1.record()
-                gemm_events.append((case, e0, e1))
+                gemm_events.append((2 * M * n * k, e0, e1))
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(record=True)
+    for k in range(args.steps):
+        step(record=k % 2)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    ops_step = sum(c.ops for c, _, _ in layers)
+    ops_step = sum(2 * M * n * k for _, n, k, _, _ in layers)
     value = ops_step / (ms_per_step * 1e-3) / 1e12
 
     gemm_ms = [e0.elapsed_time(e1) for _, e0, e1 in gemm_events]
-    gemm_ops = [c.ops for c, _, _ in gemm_events]
+    gemm_ops = [ops for ops, _, _ in gemm_events]
     avg_ms = float(np.mean(gemm_ms))
     achieved = float(np.mean(gemm_ops)) / (avg_ms * 1e-3) / 1e12
     roofline = {"kernel": "linear_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 1),
@@ -128,8 +142,8 @@ def main():
     for name, rows, K in (("gate_up_input", M, gate.K), ("down_input", M, down.K)):
         dense[name] = torch.randint(0, 256, (fptq.fptq_packed_bytes(rows, K),), dtype=torch.uint8, device=dev)
     def dense_pass():
-        for i, (case, wq, s_w) in enumerate(layers):
-            fptq.fptq_w4a4_linear(dense["gate_up_input" if i < 2 else "down_input"], wq, M, case.N, case.K, 1.0, s_w, out=ys[i])
+        for i, (name, n, k, wq, s_w) in enumerate(layers):
+            fptq.fptq_w4a4_linear(dense["gate_up_input" if i == 0 else "down_input"], wq, M, n, k, 1.0, s_w, out=ys[i])
     for _ in range(3):
         dense_pass()
     torch.cuda.synchronize()
@@ -141,14 +155,25 @@ def main():
     torch.cuda.synchronize()
     dense_tops = ops_step / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12
 
+    # gate and up as two launches of 11008 channels each (what the single fused launch replaces)
+    y_sep = torch.empty((M, gate.N), dtype=torch.bfloat16, device=dev)
+    def separate_pass():
+        for case, wq, s_w in separate:
+            fptq.fptq_w4a4_linear(xq_gu, wq, M, case.N, case.K, s_gu, s_w, out=y_sep)
+    sep_us = graph_time_us(torch, separate_pass, iters=10, replays=3)
+    fused_us = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq_gu, layers[0][3], M, layers[0][1], layers[0][2], s_gu, layers[0][4], out=ys[0]), iters=10, replays=3)
+    del y_sep, separate
+
     out = {"metric": "W4A4 linear TOPS (prefill)", "value": round(value, 1), "unit": "TOP/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 MFMA on int4 operands, int32 accumulate",
            "data": "synthetic",
-           "config": {"workload": "c2: Llama-2-7B-shaped MLP, prefill 2048 tokens: quantize X, gate and up [11008x4096], "
-                                  "quantize X_down, down [4096x11008]", "tokens": M, "ops_per_step": ops_step},
+           "config": {"workload": "c2: Llama-2-7B-shaped MLP, prefill 2048 tokens: quantize X, gate and up [11008x4096 each, "
+                                  "packed as one 22016x4096 weight, one launch], quantize X_down, down [4096x11008]",
+                      "tokens": M, "ops_per_step": ops_step},
            "pct_int8_mfma_peak": round(value / INT8_MFMA_PEAK_TOPS * 100, 2),
            "gemm_only_dense_int4_activations_tops": round(dense_tops, 1),
+           "gate_up_us": {"one_launch_22016": round(fused_us, 1), "two_launches_11008": round(sep_us, 1)},
            "roofline": roofline}
 
     # ------------------------------------------------------------------ activation-side kernels and the widened rows
@@ -172,7 +197,40 @@ def main():
                                "kind": "oracle", "seconds": round(cpu_s, 2),
                                "sample": "the full c2 step once (2048 tokens, three linears, quantizer included; weight "
                                          "generation excluded)"}
+    if args.shapes_out:
+        del layers, ys, x_gu, x_dn, xq_gu, xq_dn
+        torch.cuda.empty_cache()
+        with open(args.shapes_out, "w") as f:
+            json.dump(all_prefill_shapes(torch, fptq, synth, dev, dev_bf16), f, indent=1)
     print(json.dumps(out))
+
+
+def all_prefill_shapes(torch, fptq, synth, dev, dev_bf16):
+    """Every prefill linear of c2, c3, c5: TOP/s of fptq_w4a4_linear on the configuration's own quantized
+    activations and on uniform random INT4 activations (graph replay, 10 calls)."""
+    rows = []
+    for cfg in ("c2", "c3", "c5"):
+        for case in synth.config_cases(cfg):
+            inp = synth.draw(case, with_weights=False)
+            x = dev_bf16(inp.x_bits)
+            r_in = None if inp.row_scale_in is None else torch.from_numpy(inp.row_scale_in).to(dev)
+            xq, _ = fptq.fptq_quantize_act(x, float(inp.s_a), case.mode, case.eps, r_in)
+            nonzero = float((fptq.fptq_unpack(xq, case.M, case.K) != 0).float().mean())
+            del x, inp
+            wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(case.N, case.K),), dtype=torch.uint8, device=dev)
+            s_w = torch.rand(case.N, device=dev) * 0.015 + 0.005
+            y = torch.empty((case.M, case.N), dtype=torch.bfloat16, device=dev)
+            us_own = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq, wq, case.M, case.N, case.K, 0.5, s_w, out=y), iters=10, replays=3)
+            xd = torch.randint(0, 256, (xq.numel(),), dtype=torch.uint8, device=dev)
+            us_dense = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xd, wq, case.M, case.N, case.K, 0.5, s_w, out=y), iters=10, replays=3)
+            rows.append({"case": case.key, "M": case.M, "N": case.N, "K": case.K, "nonzero_activation_fraction": round(nonzero, 4),
+                         "own_activations": {"us": round(us_own, 1), "TOPS": round(case.ops / us_own / 1e6, 1),
+                                             "pct_peak": round(case.ops / us_own / 1e6 / INT8_MFMA_PEAK_TOPS * 100, 1)},
+                         "uniform_int4_activations": {"us": round(us_dense, 1), "TOPS": round(case.ops / us_dense / 1e6, 1),
+                                                      "pct_peak": round(case.ops / us_dense / 1e6 / INT8_MFMA_PEAK_TOPS * 100, 1)}})
+            del xq, xd, wq, y
+            torch.cuda.empty_cache()
+    return rows
 
 
 def graph_time_us(torch, fn, iters=20, replays=5):
@@ -217,12 +275,12 @@ def activation_summary(torch, fptq, dev, x_gu, x_dn, r_dn, s_gu, s_dn, gate, dow
     x_next = torch.empty_like(x_gu)
     y_blk = (torch.randn(x_gu.shape, device=dev) * 0.5).to(torch.bfloat16)
     entry("residual_norm_quantize_2048x4096", graph_time_us(torch, lambda: fptq.fptq_residual_norm_quantize(x_gu, y_blk, s_gu, None, gate.eps, x_next=x_next, s_next=r_out, out=xq_a)), M * gate.K * 6.5 + 4 * M)
-    case, wq, s_w = layers[2]
-    wsum = torch.zeros(case.N, dtype=torch.int32, device=dev)
-    us = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear_zp(xq_dn, wq, M, case.N, case.K, s_dn, s_w, 3, wsum, out=ys[2]))
-    res["down_linear_zero_point_epilogue"] = {"us": round(us, 2), "TOPS": round(case.ops / us / 1e6, 1)}
-    us = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq_dn, wq, M, case.N, case.K, s_dn, s_w, out=ys[2]))
-    res["down_linear_symmetric"] = {"us": round(us, 2), "TOPS": round(case.ops / us / 1e6, 1)}
+    _, n_dn, k_dn, wq, s_w = layers[1]
+    wsum = torch.zeros(n_dn, dtype=torch.int32, device=dev)
+    us = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear_zp(xq_dn, wq, M, n_dn, k_dn, s_dn, s_w, 3, wsum, out=ys[1]))
+    res["down_linear_zero_point_epilogue"] = {"us": round(us, 2), "TOPS": round(2 * M * n_dn * k_dn / us / 1e6, 1)}
+    us = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq_dn, wq, M, n_dn, k_dn, s_dn, s_w, out=ys[1]))
+    res["down_linear_symmetric"] = {"us": round(us, 2), "TOPS": round(2 * M * n_dn * k_dn / us / 1e6, 1)}
     return res
 
 

@@ -406,22 +406,27 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     // of all rows (rows * 64 bytes) must fit a 32-bit buffer descriptor.  Beyond them the simple
     // kernel answers.
     if (K > 131071 || (wsum && K > 65535) || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    // Tile shapes (all 4 waves, 4-stage ring).  The 256 x 256 tile has the best operand reuse; the
-    // other two exist for shapes whose 256 x 256 tile count fills the 256 CUs badly.
+    // Tile shapes (all 4 waves).  The 256 x 256 tile has the best operand reuse and wins for long K;
+    // 256 x 128 with two workgroups per CU hides prologue and epilogue and fills partial rounds, and
+    // wins elsewhere; the other two are kept for shapes neither fits.
     typedef GemmCfg<2, 2, 4, 4, 4> T256x256;   // waves of 128 x 128
     typedef GemmCfg<2, 2, 3, 4, 4> T192x256;   // BN = 192: waves of 96 (n) x 128 (m)
     typedef GemmCfg<2, 2, 4, 2, 4> T256x128;   // BM = 128: waves of 128 (n) x 64 (m)
     typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;   // the same tile, two workgroups per CU
-    // Estimated time = tile waves over the 256 CUs x tile area x a per-shape factor fitted to
-    // measurements (smaller wave tiles spend more LDS reads and issue slots per MFMA).  With two
-    // workgroups per CU the tail is filled dynamically, so its wave count is not rounded up.
+    // Estimated time in microseconds, fitted to measurements on uniform random operands (the clock is
+    // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
+    // one-workgroup-per-CU shapes run ceil(tiles / 256) rounds of (fixed + per-K-tile) each.  With two
+    // workgroups per CU the older one is served first, so epilogues overlap the other's main loop and
+    // a partial last round of r * 512 tiles costs about 0.5 + 0.15 r of a full one instead of 1.
     auto tiles = [&](int64_t bn, int64_t bm) { return (double)(((N + bn - 1) / bn) * ((M + bm - 1) / bm)); };
-    const double CUS = 256.0;
+    const double kt = (double)k_tiles(K), CUS = 256.0;
+    const double x = tiles(256, 128) / (2 * CUS), frac = x - floor(x);
+    const double rounds_o2 = floor(x) + (frac > 0 ? fmax(frac, 0.5 + 0.15 * frac) : 0.0);
     const double cost[4] = {
-        ceil(tiles(256, 256) / CUS) * 256.0 * 256.0,
-        ceil(tiles(192, 256) / CUS) * 192.0 * 256.0 * 1.06,
-        ceil(tiles(256, 128) / CUS) * 256.0 * 128.0 * 1.12,
-        fmax(1.0, tiles(256, 128) / (2 * CUS)) * 2.0 * 256.0 * 128.0 * 1.10,
+        ceil(tiles(256, 256) / CUS) * (12.9 + 1.235 * kt),
+        ceil(tiles(192, 256) / CUS) * (11.0 + 0.900 * kt),
+        ceil(tiles(256, 128) / CUS) * (9.4 + 0.667 * kt),
+        rounds_o2 * (7.8 + 1.304 * kt),
     };
     int pick = g_forced_tile > 0 ? g_forced_tile - 1 : 0;
     if (g_forced_tile <= 0)
