@@ -29,6 +29,14 @@ INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA, TOP/s
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, GB/s
 
 
+# HBM-side bytes per GEMM launch of the timed region (mean of the gate+up and the down launch), from the
+# FETCH_SIZE and WRITE_SIZE counter passes summarised in profiles/bench_c2_mlp_and_decode.md (reads scaled by
+# 2.0, writes by 1.0, the factors a 1 GiB elementwise add calibrates).  Offline figures: counters cannot be
+# read from inside this script.  The algorithmic bytes are the packed operands, the scales and the bf16 output.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 237.2e6
+GEMM_ALGORITHMIC_BYTES_PER_LAUNCH = 95079424
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,7 +143,8 @@ def main():
     achieved = float(np.mean(gemm_ops)) / (avg_ms * 1e-3) / 1e12
     roofline = {"kernel": "linear_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 1),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
-                "avg_launch_us": round(avg_ms * 1e3, 2), "ops_per_launch": int(np.mean(gemm_ops)), "traffic": None}
+                "avg_launch_us": round(avg_ms * 1e3, 2), "ops_per_launch": int(np.mean(gemm_ops)),
+                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "traffic_unit": "bytes per launch (algorithmic: %d)" % GEMM_ALGORITHMIC_BYTES_PER_LAUNCH}
 
     # the same three GEMMs on uniform random INT4 activations (dense operands draw more power)
     dense = {}
