@@ -280,6 +280,16 @@ def activation_summary(torch, fptq, dev, x_gu, x_dn, r_dn, s_gu, s_dn, gate, dow
     entry("quantize_rms_2048x4096", graph_time_us(torch, lambda: fptq.fptq_quantize_act(x_gu, s_gu, gate.mode, gate.eps, None, out=xq_a, row_scale_out=r_out)), b_a)
     entry("quantize_given_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act(x_dn, s_dn, down.mode, down.eps, r_dn, out=xq_b, row_scale_out=r_out)), b_b)
     entry("hadamard256_quantize_given_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act_hadamard(x_dn, s_dn, 256, down.mode, down.eps, r_dn, out=xq_b, row_scale_out=r_out)), b_b)
+    # the Llama-3-8B down-projection input (4096 tokens x 14336), whose largest power-of-two block is 2048
+    x_l3 = torch.randn((4096, 14336), device=dev).to(torch.bfloat16)
+    xq_l3 = torch.empty(fptq.fptq_packed_bytes(4096, 14336), dtype=torch.uint8, device=dev)
+    r_l3 = torch.rand(4096, device=dev) + 0.5
+    r_o3 = torch.empty(4096, dtype=torch.float32, device=dev)
+    b_l3 = 4096 * 14336 * 2.5 + 8 * 4096
+    entry("quantize_given_4096x14336", graph_time_us(torch, lambda: fptq.fptq_quantize_act(x_l3, 0.3, down.mode, down.eps, r_l3, out=xq_l3, row_scale_out=r_o3)), b_l3)
+    entry("hadamard2048_quantize_given_4096x14336", graph_time_us(torch, lambda: fptq.fptq_quantize_act_hadamard(x_l3, 0.3, 2048, down.mode, down.eps, r_l3, out=xq_l3, row_scale_out=r_o3)), b_l3)
+    entry("hadamard256_quantize_given_4096x14336", graph_time_us(torch, lambda: fptq.fptq_quantize_act_hadamard(x_l3, 0.3, 256, down.mode, down.eps, r_l3, out=xq_l3, row_scale_out=r_o3)), b_l3)
+    del x_l3, xq_l3
     entry("dynamic_quantize_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act_dynamic(x_dn, out=xq_b, token_scale_out=r_out)), b_b)
     x_next = torch.empty_like(x_gu)
     y_blk = (torch.randn(x_gu.shape, device=dev) * 0.5).to(torch.bfloat16)

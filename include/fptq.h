@@ -90,9 +90,10 @@ int fptq_quantize_act(const void *x_bf16, int64_t M, int64_t K, int scale_mode, 
  * The same with the online Hadamard transform T_d in front of the quantizer (Sec. 3.1.4; App. D,
  * "Hadamard non-powers of 2"): every row is transformed block-wise, x' = x blockdiag(H_B / sqrt(B)),
  * then scaled, quantized and packed as above.  The inverse is merged into the weights offline.
- *   hadamard_block  B, a power of two dividing K.  This build implements B = 256 (the group size the
- *                   paper reports for the Llama-2 FFN width 11008 = 43 * 256); anything else, or a K
- *                   that 256 does not divide, returns FPTQ_ERR_SHAPE.  x_bf16 must be 16-byte aligned.
+ *   hadamard_block  B, a power of two dividing K: 256, 512, 1024, 2048 or 4096 (the paper takes the largest
+ *                   power of two dividing the width: 256 for 11008 = 43 * 256, 2048 for 14336, 4096 for
+ *                   28672); anything else, or a K that B does not divide, returns FPTQ_ERR_SHAPE.
+ *                   x_bf16 must be 16-byte aligned.
  *   FPTQ_SCALE_RMS takes S_t from the untransformed row (what the norm layer computes).
  * Arithmetic: in-place butterflies in fp32 with strides B/2, ..., 1, each pair (a, b) -> (a + b, a - b);
  * c_t = (S_t * (1.0f / s_a)) * (float)(1 / sqrt(B)); q = clamp(rne(h * c_t), -8, 7).

@@ -126,8 +126,11 @@ static int quantize_common(const char *fn, int hadamard_block, int zero_point, c
     }
     int rc = check_dims(fn, M, K, "M", "K");
     if (rc) return rc;
-    if (hadamard_block != 0 && (hadamard_block != 256 || K % 256 != 0)) {
-        set_error("%s: hadamard_block must be 256 and divide K (got block %d, K %lld)", fn, hadamard_block, (long long)K);
+    const bool block_ok = hadamard_block == 256 || hadamard_block == 512 || hadamard_block == 1024 || hadamard_block == 2048 ||
+                          hadamard_block == 4096;
+    if (hadamard_block != 0 && (!block_ok || K % hadamard_block != 0)) {
+        set_error("%s: hadamard_block must be 256, 512, 1024, 2048 or 4096 and divide K (got block %d, K %lld)", fn, hadamard_block,
+                  (long long)K);
         return FPTQ_ERR_SHAPE;
     }
     if (scale_mode != FPTQ_SCALE_NONE && scale_mode != FPTQ_SCALE_RMS && scale_mode != FPTQ_SCALE_GIVEN) {
@@ -152,7 +155,7 @@ static int quantize_common(const char *fn, int hadamard_block, int zero_point, c
     // the one fp32 division of the quantizer happens here, on the host
     volatile float inv = 1.0f / s_a;
     hipError_t e = hadamard_block
-                       ? launch_quantize_act_hadamard((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv,
+                       ? launch_quantize_act_hadamard((const uint16_t *)x_bf16, M, K, hadamard_block, scale_mode, eps, row_scale_in, inv,
                                                       (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream)
                        : launch_quantize_act((const uint16_t *)x_bf16, M, K, scale_mode, eps, row_scale_in, inv, zero_point,
                                              (uint8_t *)xq_packed, row_scale_out, (hipStream_t)stream);
@@ -229,7 +232,7 @@ int fptq_quantize_act_hadamard(const void *x_bf16, int64_t M, int64_t K, int had
                                float *row_scale_out, void *stream)
 {
     if (hadamard_block == 0) {
-        set_error("fptq_quantize_act_hadamard: hadamard_block must be 256");
+        set_error("fptq_quantize_act_hadamard: hadamard_block must be 256, 512, 1024, 2048 or 4096");
         return FPTQ_ERR_SHAPE;
     }
     return quantize_common("fptq_quantize_act_hadamard", hadamard_block, 0, x_bf16, M, K, scale_mode, eps, row_scale_in, s_a,

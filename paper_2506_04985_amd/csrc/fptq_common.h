@@ -30,8 +30,8 @@ hipError_t launch_residual_norm_quantize(const uint16_t *xr, const uint16_t *yb,
                                          float eps, float inv_s_a, uint16_t *x_next, float *s_next, uint8_t *out, hipStream_t s);
 hipError_t launch_weight_row_sums(const int8_t *w, int64_t N, int64_t K, int32_t *sums, hipStream_t s);
 hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, uint8_t *out, float *s_out, hipStream_t s);
-hipError_t launch_quantize_act_hadamard(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in,
-                                        float inv_s_a, uint8_t *out, float *row_out, hipStream_t s);
+hipError_t launch_quantize_act_hadamard(const uint16_t *x, int64_t M, int64_t K, int hadamard_block, int mode, float eps,
+                                        const float *row_in, float inv_s_a, uint8_t *out, float *row_out, hipStream_t s);
 hipError_t launch_linear_ref(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                              hipStream_t s);

@@ -36,6 +36,33 @@ def test_hadamard_quantizer_bit_exact(oracle, mode, M, K):
     assert q_ref.min() == -8 and q_ref.max() == 7 and (q_ref != 0).mean() > 0.3
 
 
+@pytest.mark.parametrize("mode", [synth.MODE_NONE, synth.MODE_RMS, synth.MODE_GIVEN])
+@pytest.mark.parametrize("M,K,B", [(1, 512, 512), (5, 1536, 512), (3, 1024, 1024), (6, 3072, 1024), (2, 2048, 2048), (9, 14336, 2048),
+                                   (1, 4096, 4096), (7, 28672, 4096), (130, 8192, 4096), (66, 4096, 2048), (37, 4096, 1024),
+                                   (21, 4096, 512), (4, 11008, 256)])
+def test_hadamard_block_sizes_bit_exact(oracle, mode, M, K, B):
+    """Every supported block size, including the largest power of two dividing the down-projection widths of the
+    Llama-3 shapes (2048 for 14336, 4096 for 28672): same stage order as the definition, so bit-exact."""
+    inp = synth.draw(case(M, K, mode, seed=M * 5 + K + B), with_weights=False)
+    xb = inp.x_bits
+    r_ref = oracle.row_scale(xb, mode, 1e-5, inp.row_scale_in)
+    h = oracle.hadamard_rows(xb, B).astype(np.float64) / np.sqrt(B)
+    if mode != synth.MODE_NONE:
+        h = h * r_ref.astype(np.float64)[:, None]
+    s_a = np.float32(np.abs(h).max() / 7.0 * 0.6)
+    xq, r = fptq.fptq_quantize_act_hadamard(dev_bf16(xb), float(s_a), B, mode, 1e-5, dev(inp.row_scale_in))
+    q = fptq.fptq_unpack(xq, M, K).cpu().numpy()
+    q_ref = oracle.quantize_hadamard(xb, s_a, B, None if mode == synth.MODE_NONE else r_ref)
+    assert np.array_equal(r.cpu().numpy().view(np.uint32), r_ref.view(np.uint32))
+    assert np.array_equal(q, q_ref)
+    assert q_ref.min() == -8 and q_ref.max() == 7 and (q_ref != 0).mean() > 0.3
+    assert largest_block_matches(K, B)
+
+
+def largest_block_matches(K, B):
+    return K % B == 0 and B <= T.largest_pow2_divisor(K)
+
+
 def test_hadamard_path_is_function_preserving_end_to_end(oracle):
     """x W_d computed as quantize(x T_d) against quantize(T_d^T W_d): integer accumulators bit-exact against the
     oracle, and the dequantised output close to the float product although x has outlier channels."""
@@ -73,7 +100,7 @@ def test_hadamard_shape_errors():
         fptq.fptq_quantize_act_hadamard(x, 1.0, 256, synth.MODE_NONE)      # 256 does not divide 384
     assert e.value.code == -2
     x = torch.zeros((4, 512), dtype=torch.bfloat16, device="cuda")
-    for blk in (0, 128, 512):
+    for blk in (0, 128, 384, 1024, 8192):                                  # unsupported, or not a divisor of 512
         with pytest.raises(fptq.FptqError) as e:
             fptq.fptq_quantize_act_hadamard(x, 1.0, blk, synth.MODE_NONE)
         assert e.value.code == -2
