@@ -140,15 +140,20 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
 {
     // Limits: M <= 32; 256 * acc must stay in int32; the grid is one workgroup per 16 channels.
     if (M > 32 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    // K split: 16 waves per workgroup when K is long (each wave keeps at least four K tiles), so that
-    // small-N / large-K matrices still put enough loads in flight on every CU; 8 otherwise.
-    const bool wide = k_tiles(K) >= 64;
+    // Shapes chosen by measurement on the Llama-3-8B matrices (graph replay over cold weights).  16 waves
+    // split K whenever there are at least two K tiles per wave: small-N matrices then still put enough
+    // loads in flight on every CU.  Wide matrices (N >= 16384) have workgroups to spare and take 32
+    // channels per workgroup with 8 waves, which halves the activation re-reads; with more than 16
+    // tokens the same holds from N = 6144 on.
+    const bool deep = k_tiles(K) >= 32;
     if (M <= 16) {
-        if (wide) return launch_decode_cfg<16, 8, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+        if (N >= 16384) return launch_decode_cfg<8, 2, 1, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+        if (deep) return launch_decode_cfg<16, 4, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
         return launch_decode_cfg<8, 4, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     }
-    if (N >= 16384) return launch_decode_cfg<8, 4, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (wide) return launch_decode_cfg<16, 8, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (N >= 16384) return launch_decode_cfg<8, 2, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (deep && N >= 6144) return launch_decode_cfg<16, 4, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (deep) return launch_decode_cfg<16, 4, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     return launch_decode_cfg<8, 4, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 
