@@ -255,9 +255,11 @@ static hipError_t launch_wide(const uint16_t *x, int64_t M, int64_t K, int mode,
 #define FPTQ_LAUNCH_WIDE(MODE)                                                                                             \
     do {                                                                                                                   \
         auto kern = quantize_act_hadamard_wide_kernel<MODE, V>;                                                            \
-        if (LDS_BYTES > 65536) {                                                                                           \
+        static bool attr_set = false; /* more than 64 KB of dynamic LDS has to be asked for once */                         \
+        if (LDS_BYTES > 65536 && !attr_set) {                                                                              \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
             if (e != hipSuccess) return e;                                                                                 \
+            attr_set = true;                                                                                               \
         }                                                                                                                  \
         kern<<<grid, block, LDS_BYTES, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out);                           \
     } while (0)
