@@ -9,7 +9,7 @@ from paper_2506_04985_amd import synth
 def test_matches_the_kronecker_definition_exactly_on_small_integers(oracle):
     """Small integer inputs: every partial sum is exact in fp32, so the butterflies must equal x H."""
     rng = np.random.default_rng(0)
-    for K, B in [(8, 8), (64, 16), (768, 256), (11008 // 43 * 3, 256), (2048, 1024)]:
+    for K, B in [(8, 8), (64, 16), (768, 256), (11008 // 43 * 3, 256), (2048, 1024), (1024, 512), (4096, 2048), (4096, 4096)]:
         x = rng.integers(-8, 9, (5, K)).astype(np.float32)
         h = oracle.hadamard_rows(synth.f32_to_bf16_bits(x), B)
         Hb = T.block_hadamard_matrix(K, B) * np.sqrt(B)
