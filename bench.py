@@ -137,6 +137,10 @@ def main():
     ops_step = sum(2 * M * n * k for _, n, k, _, _ in layers)
     value = ops_step / (ms_per_step * 1e-3) / 1e12
 
+    per_launch = {}
+    for (name, _, _, _, _), idx in zip(layers, range(len(layers))):
+        t_us = sorted(e0.elapsed_time(e1) * 1e3 for k, (_, e0, e1) in enumerate(gemm_events) if k % len(layers) == idx)
+        per_launch[name] = {"n": len(t_us), "median_us": round(t_us[len(t_us) // 2], 2), "best_us": round(t_us[0], 2)}
     gemm_ms = [e0.elapsed_time(e1) for _, e0, e1 in gemm_events]
     gemm_ops = [ops for ops, _, _ in gemm_events]
     avg_ms = float(np.mean(gemm_ms))
@@ -144,7 +148,7 @@ def main():
     roofline = {"kernel": "linear_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 1),
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
                 "avg_launch_us": round(avg_ms * 1e3, 2), "ops_per_launch": int(np.mean(gemm_ops)),
-                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "traffic_unit": "bytes per launch (algorithmic: %d)" % GEMM_ALGORITHMIC_BYTES_PER_LAUNCH}
+                "launches": per_launch, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "traffic_unit": "bytes per launch (algorithmic: %d)" % GEMM_ALGORITHMIC_BYTES_PER_LAUNCH}
 
     # the same three GEMMs on uniform random INT4 activations (dense operands draw more power)
     dense = {}
