@@ -179,6 +179,21 @@ int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M,
  * on it. */
 int fptq_set_gemm_tile(int tile);
 
+/*
+ * Measurement aids (not part of the method): loops with nothing but the resource being measured, so a
+ * benchmark can report the rate the device sustains next to the kernels' own, from the same run.
+ *
+ * fptq_probe_mfma_rate: 256 workgroups of 4 waves, each wave issuing iters x 64 v_mfma_i32_32x32x32_i8 on
+ *   register operands (dense = 0: all zero; otherwise random nibbles in the high half of every byte, the
+ *   operand form of the prefill kernel).  out: device, 65536 int32, receives a checksum per thread.
+ *   Returns the number of integer operations launched (> 0), or a negative FPTQ_ERR_* code.  The caller
+ *   times the launch.
+ * fptq_probe_read: streams `bytes` (a multiple of 16; src 16-byte aligned) once and XORs all 16-byte words
+ *   into xor4 (device, 4 int32, which the caller zeroes first), component by component.
+ */
+int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream);
+int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream);
+
 /* Library layout -> one int8 per value, [rows x K] row-major (for parity checks and debugging). */
 int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream);
 

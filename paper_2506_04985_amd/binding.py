@@ -19,7 +19,8 @@ ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4:
 EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
            "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic", "fptq_quantize_act_asym",
            "fptq_weight_row_sums", "fptq_w4a4_linear_zp", "fptq_residual_norm_quantize",
-           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile"]
+           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile",
+           "fptq_probe_mfma_rate", "fptq_probe_read"]
 
 _lib = None
 
@@ -66,6 +67,10 @@ def lib():
         L.fptq_set_gemm_tile.argtypes = [i32]
         L.fptq_unpack.restype = i32
         L.fptq_unpack.argtypes = [p, i64, i64, p, p]
+        L.fptq_probe_mfma_rate.restype = i64
+        L.fptq_probe_mfma_rate.argtypes = [i32, i32, p, p]
+        L.fptq_probe_read.restype = i32
+        L.fptq_probe_read.argtypes = [p, i64, p, p]
         _lib = L
     return _lib
 
@@ -236,3 +241,22 @@ def fptq_unpack(packed, rows, K):
     out = torch.empty((rows, K), dtype=torch.int8, device=packed.device)
     _check(lib().fptq_unpack(_ptr(packed), rows, K, _ptr(out), _stream()))
     return out
+
+
+def fptq_probe_mfma_rate(iters, dense, out=None):
+    """Launch the MFMA-only loop; returns (integer operations launched, per-thread checksums).  The caller times it."""
+    out = torch.empty(65536, dtype=torch.int32, device="cuda") if out is None else out
+    _dev(out, torch.int32, "out")
+    ops = lib().fptq_probe_mfma_rate(int(iters), int(bool(dense)), _ptr(out), _stream())
+    if ops < 0:
+        _check(int(ops))
+    return int(ops), out
+
+
+def fptq_probe_read(src, xor4=None):
+    """Stream a device buffer once; returns the XOR of its 16-byte words as 4 int32 (xor4 is zeroed here if not given)."""
+    if not src.is_cuda or not src.is_contiguous():
+        raise TypeError("src must be a contiguous CUDA tensor")
+    xor4 = torch.zeros(4, dtype=torch.int32, device=src.device) if xor4 is None else xor4
+    _check(lib().fptq_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(xor4), _stream()))
+    return xor4

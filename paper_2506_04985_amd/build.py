@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(CSRC, "libfptq.so")
-SOURCES = ["fptq_api.hip", "fptq_pack.hip", "fptq_quant.hip", "fptq_gemm.hip", "fptq_gemv.hip", "fptq_hadamard.hip", "fptq_residual.hip"]
+SOURCES = ["fptq_api.hip", "fptq_pack.hip", "fptq_quant.hip", "fptq_gemm.hip", "fptq_gemv.hip", "fptq_hadamard.hip", "fptq_residual.hip", "fptq_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -284,6 +284,42 @@ int fptq_set_gemm_tile(int tile)
     return FPTQ_OK;
 }
 
+int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream)
+{
+    const char *fn = "fptq_probe_mfma_rate";
+    if (!out) {
+        set_error("%s: NULL pointer", fn);
+        return FPTQ_ERR_NULL;
+    }
+    if (iters < 1 || iters > (1 << 20)) {
+        set_error("%s: iters must be in [1, 2^20]", fn);
+        return FPTQ_ERR_VALUE;
+    }
+    int rc = check_align(fn, out, 4, "out");
+    if (rc) return rc;
+    hipError_t e = launch_probe_mfma(iters, dense != 0, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    // workgroups x waves x iterations x MFMAs per iteration x operations of one 32x32x32 MFMA
+    return (int64_t)PROBE_MFMA_WORKGROUPS * 4 * iters * 64 * (2 * 32 * 32 * 32);
+}
+
+int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream)
+{
+    const char *fn = "fptq_probe_read";
+    if (!src || !xor4) {
+        set_error("%s: NULL pointer", fn);
+        return FPTQ_ERR_NULL;
+    }
+    if (bytes < 16 || bytes % 16 != 0) {
+        set_error("%s: bytes must be a positive multiple of 16 (got %lld)", fn, (long long)bytes);
+        return FPTQ_ERR_SHAPE;
+    }
+    int rc;
+    if ((rc = check_align(fn, src, 16, "src")) || (rc = check_align(fn, xor4, 4, "xor4"))) return rc;
+    hipError_t e = launch_probe_read(src, bytes, xor4, (hipStream_t)stream);
+    return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
+}
+
 int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream)
 {
     if (!packed || !out_int8) {

@@ -44,6 +44,11 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
 
 void set_gemm_tile(int tile);
 
+// measurement aids (fptq_probe.hip): one workgroup of four waves per CU of the device
+constexpr int PROBE_MFMA_WORKGROUPS = 256;
+hipError_t launch_probe_mfma(int iters, int dense, int32_t *out, hipStream_t s);
+hipError_t launch_probe_read(const void *src, int64_t bytes, int32_t *xor4, hipStream_t s);
+
 // fp32 -> bf16 bit pattern, round to nearest even (NaN stays a quiet NaN)
 __device__ inline uint16_t bf16_rne(float f)
 {

@@ -1,0 +1,97 @@
+// Measurement aids: what the matrix pipe and the memory system of the device sustain for loops with
+// nothing else in them, so that a benchmark can put the kernels' rates next to the attainable ones
+// measured on the same device in the same run.  Nothing here is part of the quantized linear layer.
+#include "fptq_common.h"
+
+namespace fptq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+__device__ inline uint32_t probe_hash(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// 64 v_mfma_i32_32x32x32_i8 per iteration and wave on 16 independent accumulators, operands held in
+// registers: all zero, or random nibbles in the high half of every byte (the prefill kernel's 16 * v).
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int dense, int32_t *__restrict__ out)
+{
+    v4i a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t s = threadIdx.x * 64 + i * 4 + c + blockIdx.x * 77777u;
+            a[i][c] = dense ? (int)(probe_hash(s) & 0xF0F0F0F0u) : 0;
+            b[i][c] = dense ? (int)(probe_hash(s + 1234567u) & 0xF0F0F0F0u) : 0;
+        }
+    v16i acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[i][q] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i >> 2], b[i & 3], acc[i], 0, 0, 0);
+    }
+    int32_t r = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) r ^= acc[i][q];
+    out[blockIdx.x * 256 + threadIdx.x] = r;
+}
+
+// Streaming read: at most PROBE_READ_WORKGROUPS workgroups walk the buffer in steps of the whole grid, every
+// thread XORing 8 16-byte words per step; one atomic per workgroup and component folds the result into
+// xor4 (few enough not to show in the time), which makes the read observable and checkable.
+constexpr int PROBE_READ_WORKGROUPS = 1024;
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const v4i *__restrict__ p, int64_t n16, int32_t *__restrict__ xor4)
+{
+    __shared__ int32_t part[4][4];
+    v4i r = {0, 0, 0, 0};
+    for (int64_t base = (int64_t)blockIdx.x * (256 * 8) + threadIdx.x; base < n16; base += (int64_t)gridDim.x * (256 * 8)) {
+        v4i v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (base + u * 256 < n16) ? p[base + u * 256] : v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) r ^= v[u];
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        int x = r[c];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off, 64);
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6][c] = x;
+    }
+    __syncthreads();
+    if (threadIdx.x < 4) {
+        const int x = part[0][threadIdx.x] ^ part[1][threadIdx.x] ^ part[2][threadIdx.x] ^ part[3][threadIdx.x];
+        if (x != 0) atomicXor(xor4 + threadIdx.x, x);
+    }
+}
+
+hipError_t launch_probe_mfma(int iters, int dense, int32_t *out, hipStream_t s)
+{
+    probe_mfma_kernel<<<dim3(PROBE_MFMA_WORKGROUPS), dim3(256), 0, s>>>(iters, dense, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_read(const void *src, int64_t bytes, int32_t *xor4, hipStream_t s)
+{
+    const int64_t n16 = bytes / 16, blocks = (n16 + 256 * 8 - 1) / (256 * 8);
+    const unsigned grid = (unsigned)(blocks < PROBE_READ_WORKGROUPS ? blocks : PROBE_READ_WORKGROUPS);
+    probe_read_kernel<<<dim3(grid), dim3(256), 0, s>>>((const v4i *)src, n16, xor4);
+    return hipGetLastError();
+}
+
+}  // namespace fptq
