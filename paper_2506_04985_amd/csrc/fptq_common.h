@@ -57,6 +57,20 @@ __device__ inline uint16_t bf16_rne(float f)
     return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
+// Core of every activation quantizer: the code q + 8 in [0, 15] of q = clamp(rne(x * c) + z, -8, 7), NaN -> z,
+// with zoff = z + 8.  v_cvt_i32_f32 saturates and turns NaN into 0, the add saturates too, so infinities and
+// huge products end at the clamp like everything else: the same integers as rounding, adding and clamping in
+// float.  XOR with 8 turns the code into the two's complement nibble (eight at a time: CODE_TO_NIBBLES).
+__device__ inline uint32_t quant_code(float x, float c, int zoff)
+{
+    const float r = __builtin_rintf(x * c);
+    int i, j;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(r));
+    asm("v_add_i32 %0, %1, %2 clamp" : "=v"(j) : "v"(i), "v"(zoff));
+    return (uint32_t)min(max(j, 0), 15);
+}
+constexpr uint32_t CODE_TO_NIBBLES = 0x88888888u;
+
 // Zero-point correction of an accumulator: sum_k (v - z) w = acc - z * sum_k w (wsum == NULL: symmetric grid).
 __device__ inline int32_t remove_zero_point(int32_t acc, int zp, const int32_t *wsum, int64_t o)
 {

@@ -34,15 +34,6 @@ constexpr int H_WAVE_LDS = 4 * H_RAW_BLK + 4 * H_F32_BLK * 4;   // 7552 bytes
 
 __device__ inline float h_bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
 
-__device__ inline uint32_t h_quant_nibble(float x, float c)
-{
-    float u = x * c;
-    float r = __builtin_rintf(u);
-    r = fminf(fmaxf(r, -8.0f), 7.0f);
-    int q = (u != u) ? 0 : (int)r;
-    return (uint32_t)q & 15u;
-}
-
 __device__ inline void butterflies16(float (&v)[16])
 {
 #pragma unroll
@@ -120,9 +111,10 @@ __global__ __launch_bounds__(256) void quantize_act_hadamard_kernel(const uint16
             uint32_t w0 = 0, w1 = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                w0 |= h_quant_nibble(v[e], c) << (4 * e);
-                w1 |= h_quant_nibble(v[8 + e], c) << (4 * e);
+                w0 |= quant_code(v[e], c, 8) << (4 * e);
+                w1 |= quant_code(v[8 + e], c, 8) << (4 * e);
             }
+            w0 ^= CODE_TO_NIBBLES, w1 ^= CODE_TO_NIBBLES;
             *reinterpret_cast<uint2 *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = make_uint2(w0, w1);
         }
     }
@@ -229,7 +221,8 @@ __global__ __launch_bounds__(256) void quantize_act_hadamard_wide_kernel(const u
         for (int i = 0; i < V / 8; ++i) {
             w[i] = 0;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) w[i] |= h_quant_nibble(v[8 * i + e], c) << (4 * e);
+            for (int e = 0; e < 8; ++e) w[i] |= quant_code(v[8 * i + e], c, 8) << (4 * e);
+            w[i] ^= CODE_TO_NIBBLES;
         }
         const int64_t k0 = sc + (int64_t)V * lane;        // V <= 128 values never straddle a K tile
         uint8_t *dst = out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2;

@@ -15,15 +15,16 @@ constexpr int QREG_CHUNKS = 16; // chunks a thread keeps in registers: rows up t
 
 __device__ inline float bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
 
-// q = clamp(rne(x * c) + z, -8, 7) as a 4-bit two's complement field; NaN -> z (the code of zero).
-// z = 0 is the symmetric grid; adding 0.0f changes nothing, so one routine serves both.
-__device__ inline uint32_t quant_nibble(float x, float c, float zpf = 0.0f)
+// Eight quantized values of one 16-byte chunk of bf16 as a packed word (value e in nibble e).
+__device__ inline uint32_t quant_chunk(const uint32_t (&w)[4], float c, int zoff)
 {
-    float u = x * c;
-    float r = __builtin_rintf(u) + zpf;
-    r = fminf(fmaxf(r, -8.0f), 7.0f);
-    int q = (u != u) ? (int)zpf : (int)r;
-    return (uint32_t)q & 15u;
+    uint32_t word = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        word |= quant_code(bf16_to_f32(w[j] & 0xffffu), c, zoff) << (8 * j);
+        word |= quant_code(bf16_to_f32(w[j] >> 16), c, zoff) << (8 * j + 4);
+    }
+    return word ^ CODE_TO_NIBBLES;
 }
 
 __device__ inline double block_sum(double v, double *lds)
@@ -47,7 +48,7 @@ __device__ inline void store_word(uint8_t *out, int64_t M, int64_t t, int64_t k0
 // VEC: K is a multiple of 8, so every row starts 16-byte aligned and chunks never straddle K.
 template <int MODE, bool VEC>
 __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K, float eps,
-                                                          const float *__restrict__ row_in, float inv_s_a, float zpf,
+                                                          const float *__restrict__ row_in, float inv_s_a, int zoff,
                                                           uint8_t *__restrict__ out, float *__restrict__ row_out)
 {
     __shared__ double red[QT / 64];
@@ -100,12 +101,7 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
             int64_t k0 = ((int64_t)i * QT + tid) * QCHUNK;
             if (k0 < Kpad) {
                 const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-                uint32_t word = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c, zpf) << (8 * j);
-                    word |= quant_nibble(bf16_to_f32(w[j] >> 16), c, zpf) << (8 * j + 4);
-                }
+                const uint32_t word = quant_chunk(w, c, zoff);
                 store_word(out, M, t, k0, k0 < K ? word : 0u);
             }
         }
@@ -115,7 +111,7 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
 #pragma unroll
             for (int i = 0; i < QCHUNK; ++i) {
                 int64_t k = k0 + i;
-                if (k < K) word |= quant_nibble(bf16_to_f32(row[k]), c, zpf) << (4 * i);   // K padding stays zero
+                if (k < K) word |= (quant_code(bf16_to_f32(row[k]), c, zoff) ^ 8u) << (4 * i);   // K padding stays zero
             }
             store_word(out, M, t, k0, word);
         }
@@ -123,23 +119,27 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
 }
 
 // One wave per row, CH 16-byte chunks per lane (K <= 512 * CH, K % 8 == 0, 16-byte aligned rows).
+typedef unsigned int q_v4u __attribute__((ext_vector_type(4)));
+constexpr int Q_RSRC_FLAGS = 0x00020000;     // raw buffer, bounds-checked: reads past num_records return zero
+
+// One wave per row, for rows of at most 512 * CH values (K % 8 == 0).  The row is read through a
+// row-sized buffer descriptor, so chunks past its end read as zero and neither the loads nor the
+// quantizer need a branch; only the store of a chunk past the padded width is masked off.
 template <int MODE, int CH>
 __global__ __launch_bounds__(QT) void quantize_act_wave_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K, float eps,
-                                                               const float *__restrict__ row_in, float inv_s_a, float zpf,
+                                                               const float *__restrict__ row_in, float inv_s_a, int zoff,
                                                                uint8_t *__restrict__ out, float *__restrict__ row_out)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t t = (int64_t)blockIdx.x * (QT / 64) + (threadIdx.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t t = (int64_t)blockIdx.x * (QT / 64) + wave;
     if (t >= M) return;
-    const uint16_t *row = x + t * K;
-    const int64_t Kpad = k_tiles(K) * KT;
+    const int Ki = (int)K, Kpad = (int)(k_tiles(K) * KT);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)(x + t * K), 0, Ki * 2, Q_RSRC_FLAGS);
 
-    uint4 regs[CH];
+    q_v4u regs[CH];
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-        int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
-        regs[i] = k0 < K ? *reinterpret_cast<const uint4 *>(row + k0) : make_uint4(0, 0, 0, 0);
-    }
+    for (int i = 0; i < CH; ++i) regs[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (i * 64 + lane) * 16, 0, 0);
     float r = 1.0f;
     if (MODE == FPTQ_SCALE_RMS) {
         double ss = 0.0;
@@ -161,19 +161,15 @@ __global__ __launch_bounds__(QT) void quantize_act_wave_kernel(const uint16_t *_
     }
     const float c = (MODE == FPTQ_SCALE_NONE) ? inv_s_a : r * inv_s_a;
     if (lane == 0 && row_out) row_out[t] = r;
+    // chunk i of lane l is values 8 (64 i + l) ..: K tile 4 i + l / 16, byte 4 (l % 16) of the row's segment
+    uint8_t *orow = out + (((int64_t)(lane >> 4) * M + t) * SEG + (lane & 15) * 4);
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-        int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
-        if (k0 < Kpad) {
-            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-            uint32_t word = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c, zpf) << (8 * j);
-                word |= quant_nibble(bf16_to_f32(w[j] >> 16), c, zpf) << (8 * j + 4);
-            }
-            store_word(out, M, t, k0, k0 < K ? word : 0u);     // K padding stays zero
-        }
+        const int k0 = (i * 64 + lane) * QCHUNK;
+        const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+        uint32_t word = quant_chunk(w, c, zoff);
+        if (k0 >= Ki) word = 0u;                              // K padding stays zero
+        if (k0 < Kpad) *reinterpret_cast<uint32_t *>(orow + (int64_t)(4 * i) * M * SEG) = word;
     }
 }
 
@@ -192,18 +188,20 @@ __global__ __launch_bounds__(QT) void quantize_act_dynamic_kernel(const uint16_t
                                                                   uint8_t *__restrict__ out, float *__restrict__ s_out)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t t = (int64_t)blockIdx.x * (QT / 64) + (threadIdx.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t t = (int64_t)blockIdx.x * (QT / 64) + wave;
     if (t >= M) return;
     const uint16_t *row = x + t * K;
     const int64_t Kpad = k_tiles(K) * KT;
 
-    uint4 regs[CH > 0 ? CH : 1];
+    q_v4u regs[CH > 0 ? CH : 1];
     uint32_t mx = 0;
-    if (CH > 0) {
+    if (CH > 0) {      // the row through a row-sized buffer descriptor: chunks past its end read as zero
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)row, 0, (int)K * 2, Q_RSRC_FLAGS);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) regs[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (i * 64 + lane) * 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
-            regs[i] = k0 < K ? *reinterpret_cast<const uint4 *>(row + k0) : make_uint4(0, 0, 0, 0);
             const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) mx = max(mx, max(abs_bits_no_nan(w[j] & 0xffffu), abs_bits_no_nan(w[j] >> 16)));
@@ -219,19 +217,14 @@ __global__ __launch_bounds__(QT) void quantize_act_dynamic_kernel(const uint16_t
     if (lane == 0) s_out[t] = s;
 
     if (CH > 0) {
+        uint8_t *orow = out + (((int64_t)(lane >> 4) * M + t) * SEG + (lane & 15) * 4);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            int64_t k0 = ((int64_t)i * 64 + lane) * QCHUNK;
-            if (k0 < Kpad) {
-                const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-                uint32_t word = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    word |= quant_nibble(bf16_to_f32(w[j] & 0xffffu), c) << (8 * j);
-                    word |= quant_nibble(bf16_to_f32(w[j] >> 16), c) << (8 * j + 4);
-                }
-                store_word(out, M, t, k0, k0 < K ? word : 0u);
-            }
+            const int k0 = (i * 64 + lane) * QCHUNK;
+            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+            uint32_t word = quant_chunk(w, c, 8);
+            if (k0 >= (int)K) word = 0u;                          // K padding stays zero
+            if (k0 < (int)Kpad) *reinterpret_cast<uint32_t *>(orow + (int64_t)(4 * i) * M * SEG) = word;
         }
     } else {
         for (int64_t k0 = (int64_t)lane * QCHUNK; k0 < Kpad; k0 += 64 * QCHUNK) {
@@ -239,7 +232,7 @@ __global__ __launch_bounds__(QT) void quantize_act_dynamic_kernel(const uint16_t
 #pragma unroll
             for (int i = 0; i < QCHUNK; ++i) {
                 int64_t k = k0 + i;
-                if (k < K) word |= quant_nibble(bf16_to_f32(row[k]), c) << (4 * i);
+                if (k < K) word |= (quant_code(bf16_to_f32(row[k]), c, 8) ^ 8u) << (4 * i);
             }
             store_word(out, M, t, k0, word);
         }
@@ -253,34 +246,52 @@ hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, 
     dim3 grid((unsigned)blocks), block(QT);
     const bool vec = K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
     const int64_t Kpad = k_tiles(K) * KT;
-    if (vec && Kpad <= 512 * 8) quantize_act_dynamic_kernel<8><<<grid, block, 0, s>>>(x, M, K, out, s_out);
-    else if (vec && Kpad <= 512 * 16) quantize_act_dynamic_kernel<16><<<grid, block, 0, s>>>(x, M, K, out, s_out);
-    else if (vec && Kpad <= 512 * 24) quantize_act_dynamic_kernel<24><<<grid, block, 0, s>>>(x, M, K, out, s_out);
-    else quantize_act_dynamic_kernel<0><<<grid, block, 0, s>>>(x, M, K, out, s_out);
+#define FPTQ_DYN_CASE(CH)                                                        \
+    if (vec && Kpad <= 512 * CH) {                                               \
+        quantize_act_dynamic_kernel<CH><<<grid, block, 0, s>>>(x, M, K, out, s_out); \
+        return hipGetLastError();                                                \
+    }
+    FPTQ_DYN_CASE(4)
+    FPTQ_DYN_CASE(8)
+    FPTQ_DYN_CASE(12)
+    FPTQ_DYN_CASE(16)
+    FPTQ_DYN_CASE(20)
+    FPTQ_DYN_CASE(22)
+    FPTQ_DYN_CASE(24)
+#undef FPTQ_DYN_CASE
+    quantize_act_dynamic_kernel<0><<<grid, block, 0, s>>>(x, M, K, out, s_out);
     return hipGetLastError();
 }
 
 template <int MODE>
 static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps, const float *row_in, float inv_s_a,
-                              float zpf, uint8_t *out, float *row_out, hipStream_t s)
+                              int zoff, uint8_t *out, float *row_out, hipStream_t s)
 {
     dim3 grid((unsigned)M), block(QT);
     const bool vec = K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
     const int64_t Kpad = k_tiles(K) * KT;
     if (vec && Kpad <= 512 * 24) {
         dim3 wgrid((unsigned)((M + QT / 64 - 1) / (QT / 64)));
-        if (Kpad <= 512 * 8)
-            quantize_act_wave_kernel<MODE, 8><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
-        else if (Kpad <= 512 * 16)
-            quantize_act_wave_kernel<MODE, 16><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
-        else
-            quantize_act_wave_kernel<MODE, 24><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
+#define FPTQ_WAVE_CASE(CH)                                                                                                  \
+    if (Kpad <= 512 * CH) {                                                                                                 \
+        quantize_act_wave_kernel<MODE, CH><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out);      \
+        return hipGetLastError();                                                                                           \
+    }
+        // chunks per lane: the smallest listed count that covers the row (22 is the Llama-2 FFN width, 21.5 * 512)
+        FPTQ_WAVE_CASE(4)
+        FPTQ_WAVE_CASE(8)
+        FPTQ_WAVE_CASE(12)
+        FPTQ_WAVE_CASE(16)
+        FPTQ_WAVE_CASE(20)
+        FPTQ_WAVE_CASE(22)
+        FPTQ_WAVE_CASE(24)
+#undef FPTQ_WAVE_CASE
         return hipGetLastError();
     }
     if (vec)
-        quantize_act_kernel<MODE, true><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
+        quantize_act_kernel<MODE, true><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out);
     else
-        quantize_act_kernel<MODE, false><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zpf, out, row_out);
+        quantize_act_kernel<MODE, false><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out);
     return hipGetLastError();
 }
 
@@ -289,9 +300,9 @@ hipError_t launch_quantize_act(const uint16_t *x, int64_t M, int64_t K, int mode
 {
     if (M > 0x7fffffff) return hipErrorInvalidValue;
     switch (mode) {
-    case FPTQ_SCALE_NONE: return launch_mode<FPTQ_SCALE_NONE>(x, M, K, eps, row_in, inv_s_a, (float)zero_point, out, row_out, s);
-    case FPTQ_SCALE_RMS: return launch_mode<FPTQ_SCALE_RMS>(x, M, K, eps, row_in, inv_s_a, (float)zero_point, out, row_out, s);
-    default: return launch_mode<FPTQ_SCALE_GIVEN>(x, M, K, eps, row_in, inv_s_a, (float)zero_point, out, row_out, s);
+    case FPTQ_SCALE_NONE: return launch_mode<FPTQ_SCALE_NONE>(x, M, K, eps, row_in, inv_s_a, zero_point + 8, out, row_out, s);
+    case FPTQ_SCALE_RMS: return launch_mode<FPTQ_SCALE_RMS>(x, M, K, eps, row_in, inv_s_a, zero_point + 8, out, row_out, s);
+    default: return launch_mode<FPTQ_SCALE_GIVEN>(x, M, K, eps, row_in, inv_s_a, zero_point + 8, out, row_out, s);
     }
 }
 

@@ -12,15 +12,7 @@ namespace fptq {
 
 __device__ inline float r_bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
 
-__device__ inline uint32_t r_quant_nibble(float z, float c)
-{
-    float u = z * c;
-    float r = __builtin_rintf(u);
-    r = fminf(fmaxf(r, -8.0f), 7.0f);
-    int q = (u != u) ? 0 : (int)r;
-    return (uint32_t)q & 15u;
-}
-
+typedef unsigned int r_v4u __attribute__((ext_vector_type(4)));
 typedef __bf16 r_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float r_float2 __attribute__((ext_vector_type(2)));
 __device__ inline uint32_t r_pack_bf16(float lo, float hi)
@@ -38,7 +30,8 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
                                                                      float *__restrict__ s_next, uint8_t *__restrict__ out)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t t = (int64_t)blockIdx.x * 4 + wave;
     if (t >= M) return;
     const uint16_t *xrow = xr + t * K, *yrow = yb + t * K;
     uint16_t *orow = x_next + t * K;
@@ -46,16 +39,18 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
 
     float z[CH > 0 ? CH : 1][8];
     double ss = 0.0;
-    if (CH > 0) {
+    if (CH > 0) {      // both rows through row-sized buffer descriptors: chunks past the end read as zero, no branches
+        const __amdgpu_buffer_rsrc_t xs = __builtin_amdgcn_make_buffer_rsrc((void *)xrow, 0, (int)K * 2, 0x00020000);
+        const __amdgpu_buffer_rsrc_t ys = __builtin_amdgcn_make_buffer_rsrc((void *)yrow, 0, (int)K * 2, 0x00020000);
+        r_v4u a[CH > 0 ? CH : 1], b[CH > 0 ? CH : 1];
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int64_t k0 = ((int64_t)i * 64 + lane) * 8;
-            uint4 a = make_uint4(0, 0, 0, 0), b = a;
-            if (k0 < K) {
-                a = *reinterpret_cast<const uint4 *>(xrow + k0);
-                b = *reinterpret_cast<const uint4 *>(yrow + k0);
-            }
-            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+            a[i] = __builtin_amdgcn_raw_buffer_load_b128(xs, (i * 64 + lane) * 16, 0, 0);
+            b[i] = __builtin_amdgcn_raw_buffer_load_b128(ys, (i * 64 + lane) * 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const uint32_t aw[4] = {a[i].x, a[i].y, a[i].z, a[i].w}, bw[4] = {b[i].x, b[i].y, b[i].z, b[i].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 z[i][2 * j] = r_bf16_to_f32(aw[j] & 0xffffu) + r_bf16_to_f32(bw[j] & 0xffffu);
@@ -77,22 +72,21 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
     const float c = inv * inv_s_a;
 
     if (CH > 0) {
+        uint8_t *prow = out + (((int64_t)(lane >> 4) * M + t) * SEG + (lane & 15) * 4);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int64_t k0 = ((int64_t)i * 64 + lane) * 8;
-            if (k0 < K) {
-                uint32_t word = 0, o[4];
+            const int k0 = (i * 64 + lane) * 8;
+            uint32_t word = 0, o[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    o[j] = r_pack_bf16(z[i][2 * j] * inv, z[i][2 * j + 1] * inv);
-                    word |= r_quant_nibble(z[i][2 * j], c) << (8 * j);
-                    word |= r_quant_nibble(z[i][2 * j + 1], c) << (8 * j + 4);
-                }
-                *reinterpret_cast<uint4 *>(orow + k0) = make_uint4(o[0], o[1], o[2], o[3]);
-                *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = word;
-            } else if (k0 < Kpad) {
-                *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = 0u;   // K padding
+            for (int j = 0; j < 4; ++j) {
+                o[j] = r_pack_bf16(z[i][2 * j] * inv, z[i][2 * j + 1] * inv);
+                word |= quant_code(z[i][2 * j], c, 8) << (8 * j);
+                word |= quant_code(z[i][2 * j + 1], c, 8) << (8 * j + 4);
             }
+            word ^= CODE_TO_NIBBLES;
+            if (k0 < (int)K) *reinterpret_cast<uint4 *>(orow + k0) = make_uint4(o[0], o[1], o[2], o[3]);
+            else word = 0u;                                      // K padding stays zero
+            if (k0 < (int)Kpad) *reinterpret_cast<uint32_t *>(prow + (int64_t)(4 * i) * M * SEG) = word;
         }
     } else {
         for (int64_t k0 = (int64_t)lane * 8; k0 < Kpad; k0 += 512) {
@@ -103,7 +97,7 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
                 if (k < K) {
                     const float v = r_bf16_to_f32(xrow[k]) + r_bf16_to_f32(yrow[k]);
                     orow[k] = (uint16_t)(r_pack_bf16(v * inv, 0.0f) & 0xffffu);
-                    word |= r_quant_nibble(v, c) << (4 * e);
+                    word |= (quant_code(v, c, 8) ^ 8u) << (4 * e);
                 }
             }
             *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = word;
@@ -119,12 +113,17 @@ hipError_t launch_residual_norm_quantize(const uint16_t *xr, const uint16_t *yb,
     dim3 grid((unsigned)blocks), block(256);
     const bool vec = K % 8 == 0 && ((reinterpret_cast<uintptr_t>(xr) | reinterpret_cast<uintptr_t>(yb) |
                                      reinterpret_cast<uintptr_t>(x_next)) & 15) == 0;
-    if (vec && K <= 512 * 8)
-        residual_norm_quantize_kernel<8><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
-    else if (vec && K <= 512 * 16)
-        residual_norm_quantize_kernel<16><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
-    else
-        residual_norm_quantize_kernel<0><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
+#define FPTQ_RES_CASE(CH)                                                                                                       \
+    if (vec && K <= 512 * CH) {                                                                                                 \
+        residual_norm_quantize_kernel<CH><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);      \
+        return hipGetLastError();                                                                                               \
+    }
+    FPTQ_RES_CASE(4)
+    FPTQ_RES_CASE(8)
+    FPTQ_RES_CASE(12)
+    FPTQ_RES_CASE(16)
+#undef FPTQ_RES_CASE
+    residual_norm_quantize_kernel<0><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
     return hipGetLastError();
 }
 
