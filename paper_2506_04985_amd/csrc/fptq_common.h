@@ -57,6 +57,14 @@ __device__ inline uint16_t bf16_rne(float f)
     return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
+// ss + v * v in fp64 for an fp32 v: the square of a value with at most 24 significant bits is exact in fp64, so the
+// fused form rounds once, exactly like the separate multiply and add of the definition.
+__device__ inline double add_square(double ss, float v)
+{
+    const double a = (double)v;
+    return __builtin_fma(a, a, ss);
+}
+
 // Core of every activation quantizer: the code q + 8 in [0, 15] of q = clamp(rne(x * c) + z, -8, 7), NaN -> z,
 // with zoff = z + 8.  v_cvt_i32_f32 saturates and turns NaN into 0, the add saturates too, so infinities and
 // huge products end at the clamp like everything else: the same integers as rounding, adding and clamping in

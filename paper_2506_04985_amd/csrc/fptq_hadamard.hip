@@ -68,8 +68,8 @@ __global__ __launch_bounds__(256) void quantize_act_hadamard_kernel(const uint16
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 double a = (double)h_bf16_to_f32(w[j] & 0xffffu), b = (double)h_bf16_to_f32(w[j] >> 16);
-                ss += a * a;
-                ss += b * b;
+                ss = __builtin_fma(a, a, ss);
+                ss = __builtin_fma(b, b, ss);
             }
         }
 #pragma unroll
@@ -179,8 +179,8 @@ __global__ __launch_bounds__(256) void quantize_act_hadamard_wide_kernel(const u
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 double a = (double)h_bf16_to_f32(w[j] & 0xffffu), b = (double)h_bf16_to_f32(w[j] >> 16);
-                ss += a * a;
-                ss += b * b;
+                ss = __builtin_fma(a, a, ss);
+                ss = __builtin_fma(b, b, ss);
             }
         }
 #pragma unroll

@@ -76,15 +76,16 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
                 const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
+                    // a * a is exact in fp64 (8 significant bits squared), so the fused form rounds like multiply, then add
                     double a = (double)bf16_to_f32(w[j] & 0xffffu), b = (double)bf16_to_f32(w[j] >> 16);
-                    ss += a * a;
-                    ss += b * b;
+                    ss = __builtin_fma(a, a, ss);
+                    ss = __builtin_fma(b, b, ss);
                 }
             }
         } else {
             for (int64_t k = tid; k < K; k += QT) {
                 double a = (double)bf16_to_f32(row[k]);
-                ss += a * a;
+                ss = __builtin_fma(a, a, ss);
             }
         }
         ss = block_sum(ss, red);
@@ -149,8 +150,8 @@ __global__ __launch_bounds__(QT) void quantize_act_wave_kernel(const uint16_t *_
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 double a = (double)bf16_to_f32(w[j] & 0xffffu), b = (double)bf16_to_f32(w[j] >> 16);
-                ss += a * a;
-                ss += b * b;
+                ss = __builtin_fma(a, a, ss);
+                ss = __builtin_fma(b, b, ss);
             }
         }
 #pragma unroll

@@ -55,14 +55,14 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
             for (int j = 0; j < 4; ++j) {
                 z[i][2 * j] = r_bf16_to_f32(aw[j] & 0xffffu) + r_bf16_to_f32(bw[j] & 0xffffu);
                 z[i][2 * j + 1] = r_bf16_to_f32(aw[j] >> 16) + r_bf16_to_f32(bw[j] >> 16);
-                ss += (double)z[i][2 * j] * (double)z[i][2 * j];
-                ss += (double)z[i][2 * j + 1] * (double)z[i][2 * j + 1];
+                ss = add_square(ss, z[i][2 * j]);
+                ss = add_square(ss, z[i][2 * j + 1]);
             }
         }
     } else {
         for (int64_t k = lane; k < K; k += 64) {
             const float v = r_bf16_to_f32(xrow[k]) + r_bf16_to_f32(yrow[k]);
-            ss += (double)v * (double)v;
+            ss = add_square(ss, v);
         }
     }
 #pragma unroll
