@@ -135,8 +135,8 @@ int fptq_quantize_act_dynamic(const void *x_bf16, int64_t M, int64_t K, void *xq
 
 /*
  * The quantized linear layer proper: INT4 x INT4 matmul with INT32 accumulation and the
- * float-scale epilogue (App. J; App. B).  Picks a few-token (bandwidth-bound) kernel for small M
- * and the INT8-MFMA GEMM otherwise.
+ * float-scale epilogue (App. J; App. B).  Picks a few-token kernel (bound by the weight read) for
+ * M <= 64, and for M <= 128 against fewer than 16384 channels, and the INT8-MFMA GEMM otherwise.
  *   xq_packed      device, packed activations [M x K] from fptq_quantize_act
  *   w_packed       device, packed weights [N x K] from fptq_pack_weights
  *   s_a            the same static activation scale given to fptq_quantize_act
@@ -175,8 +175,8 @@ int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M,
 
 /* Testing / tuning knob for the prefill kernel's tile shape (process-wide, not thread-safe against
  * concurrent fptq_w4a4_linear calls): 0 = chosen per problem (default), 1 = 256x256, 2 = 192 (N) x
- * 256 (M), 3 = 256 (N) x 128 (M), 4 = 256 x 128 with two workgroups per CU.  Results do not depend
- * on it. */
+ * 256 (M), 3 = 256 (N) x 128 (M), 4 = 256 x 128 with two workgroups per CU.  A forced shape also sends
+ * calls with few tokens to the prefill kernel.  Results do not depend on it. */
 int fptq_set_gemm_tile(int tile);
 
 /*

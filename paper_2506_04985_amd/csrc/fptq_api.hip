@@ -44,8 +44,10 @@ static int check_align(const char *fn, const void *p, unsigned a, const char *na
     return FPTQ_OK;
 }
 
-// Largest M served by the few-token kernel; above it the MFMA GEMM runs.
-static const int64_t DECODE_MAX_M = 32;
+// The few-token kernel serves M <= 64 and, for matrices of fewer than 16384 channels, M <= 128 (measured: wide
+// matrices at 65 .. 128 tokens are faster on the MFMA GEMM); above that, or whenever a prefill tile shape is
+// forced, the MFMA GEMM runs.
+static bool few_token_shape(int64_t M, int64_t N) { return M <= 64 || (M <= 128 && N < 16384); }
 
 typedef hipError_t (*linear_fn)(const uint8_t *, const uint8_t *, int64_t, int64_t, int64_t, float, const float *,
                                 const float *, int, const int32_t *, uint16_t *, int32_t *, hipStream_t);
@@ -76,7 +78,7 @@ static int linear_common(const char *fn, linear_fn force, const void *xq, const 
         return FPTQ_ERR_VALUE;
     }
     if (zp == 0) wsum = nullptr;
-    linear_fn f = force ? force : (M <= DECODE_MAX_M ? launch_linear_decode : launch_linear_mfma);
+    linear_fn f = force ? force : (few_token_shape(M, N) && forced_gemm_tile() == 0 ? launch_linear_decode : launch_linear_mfma);
     hipError_t e = f((const uint8_t *)xq, (const uint8_t *)wq, M, N, K, s_a, s_w, d, zp, wsum, (uint16_t *)y, acc,
                      (hipStream_t)stream);
     return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);

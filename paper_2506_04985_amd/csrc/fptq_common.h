@@ -43,6 +43,7 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
                                 hipStream_t s);
 
 void set_gemm_tile(int tile);
+int forced_gemm_tile();
 
 // measurement aids (fptq_probe.hip): one workgroup of four waves per CU of the device
 constexpr int PROBE_MFMA_WORKGROUPS = 256;

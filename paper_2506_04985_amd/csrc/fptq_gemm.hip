@@ -366,6 +366,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
 // 0 = choose the tile shape per problem; 1..4 = force one (testing and tuning)
 static int g_forced_tile = 0;
 void set_gemm_tile(int tile) { g_forced_tile = tile; }
+int forced_gemm_tile() { return g_forced_tile; }
 
 template <class C, bool ALIGNED, bool DUMP>
 static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,

@@ -1,4 +1,4 @@
-// Few-token (decode) kernel of the quantized linear layer: M <= 32 tokens against packed INT4
+// Few-token (decode) kernel of the quantized linear layer: M <= 128 tokens against packed INT4
 // weights, INT32 accumulation, float-scale epilogue to bf16 (App. J and App. B of the paper).
 //
 // The job is bound by reading the packed weights once from HBM, so the kernel is built around
@@ -11,10 +11,14 @@
 //     1 KB chunk (16 rows x 64 bytes) and U such loads are in flight per wave;
 //   - the activations of the same K tile (M x 64 bytes, L2 resident) are loaded the same way,
 //     token rows clamped to M - 1 (duplicate columns are computed and dropped);
-//   - v_mfma_i32_16x16x64_i8 does the arithmetic: A = 16 weight rows, B = 16 tokens (two B
-//     operands when M > 16).  Nibbles are widened to bytes exactly as in the prefill kernel
+//   - v_mfma_i32_16x16x64_i8 does the arithmetic: A = 16 weight rows, B = 16 tokens (MT B
+//     operands for up to 16 MT tokens).  Nibbles are widened to bytes exactly as in the prefill kernel
 //     (16 * value on both sides, accumulator = 256 * acc, shifted back in the epilogue);
-//   - the WAVES partial accumulators are summed through LDS (integers: exact, order-free).
+//   - the WAVES partial accumulators are added into one LDS tile with LDS atomics (integers:
+//     exact, order-free).
+// Every workgroup streams all of X, so the activation traffic from L2 grows with M: beyond 32 tokens
+// the kernel is no longer bound by the weights alone, but up to 128 tokens it still beats the prefill
+// kernel, whose 256 x 128 tiles leave most CUs idle at such M.
 #include "fptq_common.h"
 
 namespace fptq {
@@ -31,16 +35,17 @@ __device__ inline v4i dec_widen(int p0, int p1)
     return o;
 }
 
-// MT = number of 16-token groups (1: M <= 16, 2: M <= 32); RT = number of 16-channel groups per
-// workgroup (2 halves the activation re-reads per weight byte, used when M > 16 and N is large);
-// U = K tiles in flight per wave
+// MT = number of 16-token groups (M <= 16 MT); RT = number of 16-channel groups per workgroup (more of
+// them cut the activation re-reads per weight byte); U = K tiles in flight per wave
 template <int WAVES, int U, int MT, int RT>
 __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, float s_a,
     const float *__restrict__ s_w, const float *__restrict__ d, int zp, const int32_t *__restrict__ wsum,
     uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
 {
-    __shared__ int32_t red[WAVES * RT * MT * 256];     // [WAVES][RT][MT][16 tokens][16 channels]
+    __shared__ int32_t red[RT * MT * 256];             // [RT][MT][16 tokens][16 channels], summed over the waves
+    for (int o = threadIdx.x; o < RT * MT * 256; o += 64 * WAVES) red[o] = 0;
+    __syncthreads();
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n0 = blockIdx.x * (16 * RT);
@@ -100,21 +105,18 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
             }
     }
 
-    // ---- reduce the WAVES partial tiles through LDS.  D layout of the 16x16 MFMA: lane l, register
-    // r holds D[row = 4 (l / 16) + r][col = l % 16]; rows are output channels, columns tokens.
+    // ---- add the WAVES partial tiles in LDS.  D layout of the 16x16 MFMA: lane l, register r holds
+    // D[row = 4 (l / 16) + r][col = l % 16]; rows are output channels, columns tokens.
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                red[(((wave * RT + rt) * MT + mt) * 16 + fi) * 16 + 4 * fg + r] = acc[rt][mt][r];
+            for (int r = 0; r < 4; ++r) atomicAdd(&red[((rt * MT + mt) * 16 + fi) * 16 + 4 * fg + r], acc[rt][mt][r]);
     __syncthreads();
     for (int o = tid; o < RT * MT * 256; o += 64 * WAVES) {
         const int g = o >> 8, rt = g / MT, mt = g % MT, j = (o >> 4) & 15, i = o & 15;   // groups, token, channel
-        int32_t sum = 0;
-#pragma unroll
-        for (int w = 0; w < WAVES; ++w) sum += red[(((w * RT + rt) * MT + mt) * 16 + j) * 16 + i];
+        const int32_t sum = red[o];
         const int t = mt * 16 + j, n = n0 + rt * 16 + i;
         if (t < M && n < N) {
             const int32_t a = sum >> 8;                // exact: the sum is 256 * acc
@@ -138,23 +140,37 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
                                 const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                                     hipStream_t s)
 {
-    // Limits: M <= 32; 256 * acc must stay in int32; the grid is one workgroup per 16 channels.
-    if (M > 32 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    // Limits: M <= 128; 256 * acc must stay in int32; the grid is one workgroup per 16 RT channels.
+    if (M > 128 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     // Shapes chosen by measurement on the Llama-3-8B matrices (graph replay over cold weights).  16 waves
     // split K whenever there are at least two K tiles per wave: small-N matrices then still put enough
-    // loads in flight on every CU.  Wide matrices (N >= 16384) have workgroups to spare and take 32
-    // channels per workgroup with 8 waves, which halves the activation re-reads; with more than 16
-    // tokens the same holds from N = 6144 on.
+    // loads in flight on every CU.  Wide matrices (N >= 16384) have workgroups to spare and take more
+    // channels per workgroup with 8 waves, which cuts the activation re-reads; with more than 16
+    // tokens the same holds from N = 6144 on.  The register budget (128 per wave with 16 waves) bounds
+    // RT * MT and the K tiles in flight.
     const bool deep = k_tiles(K) >= 32;
+#define FPTQ_DEC(W, U, MT, RT) return launch_decode_cfg<W, U, MT, RT>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
     if (M <= 16) {
-        if (N >= 16384) return launch_decode_cfg<8, 2, 1, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-        if (deep) return launch_decode_cfg<16, 4, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-        return launch_decode_cfg<8, 4, 1, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+        if (N >= 16384) FPTQ_DEC(8, 2, 1, 2);
+        if (deep) FPTQ_DEC(16, 4, 1, 1);
+        FPTQ_DEC(8, 4, 1, 1);
     }
-    if (N >= 16384) return launch_decode_cfg<8, 2, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (deep && N >= 6144) return launch_decode_cfg<16, 4, 2, 2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (deep) return launch_decode_cfg<16, 4, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    return launch_decode_cfg<8, 4, 2, 1>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (M <= 32) {
+        if (N >= 16384) FPTQ_DEC(8, 2, 2, 2);
+        if (deep && N >= 6144) FPTQ_DEC(16, 4, 2, 2);
+        if (deep) FPTQ_DEC(16, 4, 2, 1);
+        FPTQ_DEC(8, 4, 2, 1);
+    }
+    if (M <= 64) {
+        if (N >= 16384) FPTQ_DEC(8, 2, 4, 2);
+        if (deep && N >= 6144) FPTQ_DEC(16, 2, 4, 2);
+        if (deep) FPTQ_DEC(16, 2, 4, 1);
+        FPTQ_DEC(8, 2, 4, 1);
+    }
+    if (N >= 6144) FPTQ_DEC(8, 1, 8, 2);
+    if (deep) FPTQ_DEC(16, 1, 8, 1);
+    FPTQ_DEC(8, 1, 8, 1);
+#undef FPTQ_DEC
 }
 
 }  // namespace fptq

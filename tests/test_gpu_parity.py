@@ -90,7 +90,10 @@ def test_quantize_act_special_values(oracle):
 SHAPES = [(1, 1, 2), (3, 5, 34), (128, 512, 512), (100, 300, 640), (257, 513, 1024), (33, 1000, 130),
           (300, 260, 4096), (64, 64, 128), (1, 512, 512), (8, 700, 1024), (32, 256, 4096), (31, 33, 258),
           (16, 300, 2048), (17, 48, 14336), (5, 1030, 4096), (2, 16, 128), (32, 17, 896), (9, 2000, 11008),
-          (32, 16400, 256), (20, 16390, 384), (3, 70, 8200)]
+          (32, 16400, 256), (20, 16390, 384), (3, 70, 8200),
+          # 33 .. 128 tokens: every launch shape of the few-token kernel
+          (64, 16400, 256), (50, 6200, 4096), (48, 100, 4096), (128, 16400, 256), (100, 6150, 640), (127, 300, 4224),
+          (129, 300, 640)]
 
 
 @pytest.mark.parametrize("use_ref", [False, True], ids=["tuned", "ref"])
