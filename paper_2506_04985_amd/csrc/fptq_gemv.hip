@@ -43,7 +43,7 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
     const float *__restrict__ s_w, const float *__restrict__ d, int zp, const int32_t *__restrict__ wsum,
     uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
 {
-    __shared__ int32_t red[RT * MT * 256];             // [RT][MT][16 tokens][16 channels], summed over the waves
+    __shared__ int32_t red[RT * MT * 256];             // per (rt, mt) group a 16 x 16 tile in accumulator-register order
     for (int o = threadIdx.x; o < RT * MT * 256; o += 64 * WAVES) red[o] = 0;
     __syncthreads();
     const int tid = threadIdx.x, lane = tid & 63;
@@ -112,11 +112,12 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) atomicAdd(&red[((rt * MT + mt) * 16 + fi) * 16 + 4 * fg + r], acc[rt][mt][r]);
+            for (int r = 0; r < 4; ++r)      // word 64 r + lane of the group's tile: the 64 lanes of an add hit 64 different banks
+                atomicAdd(&red[(rt * MT + mt) * 256 + r * 64 + 4 * fi + fg], acc[rt][mt][r]);
     __syncthreads();
     for (int o = tid; o < RT * MT * 256; o += 64 * WAVES) {
         const int g = o >> 8, rt = g / MT, mt = g % MT, j = (o >> 4) & 15, i = o & 15;   // groups, token, channel
-        const int32_t sum = red[o];
+        const int32_t sum = red[g * 256 + (i & 3) * 64 + 4 * j + (i >> 2)];
         const int t = mt * 16 + j, n = n0 + rt * 16 + i;
         if (t < M && n < N) {
             const int32_t a = sum >> 8;                // exact: the sum is 256 * acc
