@@ -409,11 +409,13 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     if (K > 131071 || (wsum && K > 65535) || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     // Tile shapes (all 4 waves).  The 256 x 256 tile has the best operand reuse and wins for long K;
     // 256 x 128 with two workgroups per CU hides prologue and epilogue and fills partial rounds, and
-    // wins elsewhere; the other two are kept for shapes neither fits.
+    // wins elsewhere; the 192- and one-workgroup 128-row shapes are kept for shapes neither fits; 128 x 128
+    // serves problems with very few output tiles.
     typedef GemmCfg<2, 2, 4, 4, 4> T256x256;   // waves of 128 x 128
     typedef GemmCfg<2, 2, 3, 4, 4> T192x256;   // BN = 192: waves of 96 (n) x 128 (m)
     typedef GemmCfg<2, 2, 4, 2, 4> T256x128;   // BM = 128: waves of 128 (n) x 64 (m)
     typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;   // the same tile, two workgroups per CU
+    typedef GemmCfg<2, 2, 2, 2, 3, 3> T128x128o3;   // waves of 64 x 64, three workgroups per CU
     // Estimated time in microseconds, fitted to measurements on uniform random operands (the clock is
     // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
     // one-workgroup-per-CU shapes run ceil(tiles / 256) rounds of (fixed + per-K-tile) each.  With two
@@ -430,12 +432,18 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
         rounds_o2 * (7.8 + 1.304 * kt),
     };
     int pick = g_forced_tile > 0 ? g_forced_tile - 1 : 0;
-    if (g_forced_tile <= 0)
+    if (g_forced_tile <= 0) {
         for (int i = 1; i < 4; ++i)
             if (cost[i] < cost[pick]) pick = i;
+        // Problems so small that even 128 x 128 tiles give every CU at most one workgroup: the kernel time is
+        // one workgroup's walk through K, and the small tile walks fastest (measured 19 against 25 us at
+        // K = 4096).  A deeper ring does not help there; filling the idle CUs would take a split of K.
+        if (tiles(128, 128) <= CUS) pick = 4;
+    }
     if (pick == 1) return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 2) return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 4) return launch_cfg<T128x128o3>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 
