@@ -140,7 +140,8 @@ def main():
     per_launch = {}
     for (name, _, _, _, _), idx in zip(layers, range(len(layers))):
         t_us = sorted(e0.elapsed_time(e1) * 1e3 for k, (_, e0, e1) in enumerate(gemm_events) if k % len(layers) == idx)
-        per_launch[name] = {"n": len(t_us), "median_us": round(t_us[len(t_us) // 2], 2), "best_us": round(t_us[0], 2)}
+        if t_us:          # with fewer steps than launches per step some launch is never bracketed
+            per_launch[name] = {"n": len(t_us), "median_us": round(t_us[len(t_us) // 2], 2), "best_us": round(t_us[0], 2)}
     gemm_ms = [e0.elapsed_time(e1) for _, e0, e1 in gemm_events]
     gemm_ops = [ops for ops, _, _ in gemm_events]
     avg_ms = float(np.mean(gemm_ms))
