@@ -23,6 +23,18 @@ def test_asymmetric_quantizer_bit_exact(oracle, M, K, mode, zp):
     assert np.array_equal(r.cpu().numpy().view(np.uint32), r_ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("zp", [-8, -3, 0, 5, 7])
+@pytest.mark.parametrize("s_a", [0.731, 1e-30, 3e30])
+def test_asymmetric_quantizer_every_bf16_pattern(oracle, zp, s_a):
+    """All 65536 bit patterns (NaNs, infinities, subnormals, huge and tiny magnitudes), also with scales that drive the
+    product to infinity or to zero: the saturating integer path must agree with clamping in float."""
+    allbits = np.arange(65536, dtype=np.uint16).reshape(8, 8192)
+    r = np.array([1.0, 0.5, 0.3333, 2.7, 13.37, 1e-3, 100.0, 7.0], np.float32)
+    xq, _ = fptq.fptq_quantize_act_asym(dev_bf16(allbits), s_a, zp, synth.MODE_GIVEN, 0.0, dev(r))
+    q = fptq.fptq_unpack(xq, 8, 8192).cpu().numpy()
+    assert np.array_equal(q, oracle.quantize_zp(allbits, np.float32(s_a), zp, r))
+
+
 def test_weight_row_sums(oracle):
     rng = np.random.default_rng(0)
     for N, K in [(1, 1), (5, 34), (300, 4096), (64, 11008)]:
