@@ -32,23 +32,28 @@ constexpr int WAIT_LGKM0 = 15 | (3 << 14) | (7 << 4) | (0 << 8);
 // raw buffer descriptor, dword 3: 32-bit data format, no swizzle (gfx9 family encoding)
 constexpr int RSRC_FLAGS = 0x00020000;
 
-// OCC_ = workgroups meant to share a CU (caps the register budget: 512 / OCC_ per lane)
-template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_, int OCC_ = 1>
+// OCC_ = workgroups meant to share a CU (caps the register budget: 512 / OCC_ per lane).  KS_ = K groups:
+// KS_ sets of WAVES waves work on the same output tile, set g on K tiles g, g + KS_, ..., each with its own
+// LDS ring; their accumulators are added through LDS before the epilogue.  A problem with at most one
+// workgroup per CU runs one wave per SIMD, which cannot hide its own LDS and VALU latencies; a second K group
+// gives every SIMD a second wave without needing more output tiles.
+template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_, int OCC_ = 1, int KS_ = 1>
 struct GemmCfg {
-    static constexpr int WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, TN = TN_, TM = TM_, STAGES = STAGES_, OCC = OCC_;
+    static constexpr int WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, TN = TN_, TM = TM_, STAGES = STAGES_, OCC = OCC_, KS = KS_;
     static constexpr int BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32;
-    static constexpr int WAVES = WAVES_N * WAVES_M, THREADS = 64 * WAVES;
+    static constexpr int WAVES = WAVES_N * WAVES_M, THREADS = 64 * WAVES * KS;
     static constexpr int W_BYTES = BN * SEG, X_BYTES = BM * SEG, STAGE_BYTES = W_BYTES + X_BYTES;
     // every wave copies a contiguous run of rows of each operand tile, 1 KB (16 rows) per load
     static constexpr int W_LOADS = W_BYTES / (WAVES * 1024), X_LOADS = X_BYTES / (WAVES * 1024);
     static constexpr int LOADS = W_LOADS + X_LOADS;
-    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int RING_BYTES = STAGES * STAGE_BYTES, LDS_BYTES = KS * RING_BYTES;
     static_assert(W_BYTES % (WAVES * 1024) == 0 && X_BYTES % (WAVES * 1024) == 0, "tile must split over waves");
     static_assert(W_LOADS >= 1 && W_LOADS <= 4 && X_LOADS >= 1 && X_LOADS <= 4, "the fill schedule issues at most one W and one X chunk per quarter");
     // loads issued by fill quarters 0 and 1 (a quarter q carries W chunk q and X chunk q if they exist)
     static constexpr int HALF_LOADS = (W_LOADS < 2 ? W_LOADS : 2) + (X_LOADS < 2 ? X_LOADS : 2);
     static_assert(STAGES >= 3, "pipeline needs three stages");
     static_assert(TN <= 4, "a wave's channel run must fit 16 lanes of 8 channels in the epilogue");
+    static_assert(KS == 1 || TN * TM * 16 * WAVES * 64 * 4 <= LDS_BYTES, "the K groups' accumulators are added through LDS");
 };
 
 // widen two packed dwords (16 nibbles) into one MFMA operand of 16 bytes, each 16 * value
@@ -89,8 +94,10 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = C::KS > 1 ? wave_all / C::WAVES : 0, wave = C::KS > 1 ? wave_all % C::WAVES : wave_all;   // K group, wave in it
     const int wave_n = wave % C::WAVES_N, wave_m = wave / C::WAVES_N;
+    uint8_t *const ring = lds + kg * C::RING_BYTES;                      // this K group's LDS ring
 
     // ---- tile of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs; give each XCD a
     // contiguous run of logical tiles so that its L2 sees neighbouring tiles, then walk the tile grid
@@ -123,16 +130,22 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const int w_lds0 = wave * (C::W_LOADS * 1024), x_lds0 = C::W_BYTES + wave * (C::X_LOADS * 1024);
     const int64_t w_slab = (int64_t)N * SEG, x_slab = (int64_t)M * SEG;   // bytes per K tile of all rows
 
-    // per-slab descriptors: rows past N (M) fail the bounds check and read as zero
-    auto w_desc = [&](int kt) {
-        return __builtin_amdgcn_make_buffer_rsrc((void *)(wq + kt * w_slab), 0, (int)w_slab, RSRC_FLAGS);
+    // per-slab descriptors: rows past N (M) fail the bounds check and read as zero.  Step j of this K group
+    // is K tile j * KS + kg; a step past the last tile gets an empty descriptor, so its loads are still
+    // issued (the outstanding-load count stays uniform) but read nothing and land as zeros.
+    auto w_desc = [&](int j) {
+        const int kt = j * C::KS + kg;
+        const bool in = kt < ktiles;
+        return __builtin_amdgcn_make_buffer_rsrc((void *)(wq + (in ? kt : 0) * w_slab), 0, in ? (int)w_slab : 0, RSRC_FLAGS);
     };
-    auto x_desc = [&](int kt) {
-        return __builtin_amdgcn_make_buffer_rsrc((void *)(xq + kt * x_slab), 0, (int)x_slab, RSRC_FLAGS);
+    auto x_desc = [&](int j) {
+        const int kt = j * C::KS + kg;
+        const bool in = kt < ktiles;
+        return __builtin_amdgcn_make_buffer_rsrc((void *)(xq + (in ? kt : 0) * x_slab), 0, in ? (int)x_slab : 0, RSRC_FLAGS);
     };
     // quarter q (0..3) of the fill of one K tile: W chunk q and X chunk q, where they exist
     auto fill_quarter = [&](__amdgpu_buffer_rsrc_t wr, __amdgpu_buffer_rsrc_t xr, int stage, int q) {
-        uint8_t *sb = lds + stage * C::STAGE_BYTES;
+        uint8_t *sb = ring + stage * C::STAGE_BYTES;
         if (q == 0) { load_chunk<0>(wr, sb + w_lds0, w_voff); load_chunk<0>(xr, sb + x_lds0, x_voff); }
         if (q == 1) {
             if (C::W_LOADS > 1) load_chunk<1>(wr, sb + w_lds0, w_voff);
@@ -178,11 +191,10 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     //   -- tile kt+1 has landed; barrier; every wave is done reading tile kt --
     //   G2(kt): MFMA step 2 | widen step 3 (R1 high)  | read R0(kt+1)   | fill(kt+S) quarter 0, into tile kt's buffer
     //   G3(kt): MFMA step 3 | widen step 0' (R0' low) |                 | fill(kt+S) quarter 1
-    // Tiles past the end repeat the last one, which keeps the outstanding-load count uniform.
     v4i opW[2][C::TN], opX[2][C::TM], rawW[2][C::TN], rawX[2][C::TM];
     auto read_frags = [&](int stage, int kk, v4i (&wraw)[C::TN], v4i (&xraw)[C::TM]) {
-        const uint8_t *wb = lds + stage * C::STAGE_BYTES + w_wave + frag_off[kk];
-        const uint8_t *xb = lds + stage * C::STAGE_BYTES + x_wave + frag_off[kk];
+        const uint8_t *wb = ring + stage * C::STAGE_BYTES + w_wave + frag_off[kk];
+        const uint8_t *xb = ring + stage * C::STAGE_BYTES + x_wave + frag_off[kk];
 #pragma unroll
         for (int tn = 0; tn < C::TN; ++tn) wraw[tn] = *reinterpret_cast<const v4i *>(wb + tn * (32 * SEG));
 #pragma unroll
@@ -220,16 +232,16 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    auto clampk = [&](int kt) { return min(kt, ktiles - 1); };
+    const int steps = (ktiles + C::KS - 1) / C::KS;      // the same for every K group: they share the barriers
 #pragma unroll
     for (int s = 0; s < C::STAGES - 1; ++s) {
-        __amdgpu_buffer_rsrc_t wr = w_desc(clampk(s)), xr = x_desc(clampk(s));
+        __amdgpu_buffer_rsrc_t wr = w_desc(s), xr = x_desc(s);
 #pragma unroll
         for (int q = 0; q < 4; ++q) fill_quarter(wr, xr, s, q);
     }
-    // descriptors of the fill that is half way (tile kt+S-1) and of the one that starts in G2 (tile kt+S)
-    __amdgpu_buffer_rsrc_t wr_a = w_desc(clampk(C::STAGES - 1)), xr_a = x_desc(clampk(C::STAGES - 1));
-    __amdgpu_buffer_rsrc_t wr_b = w_desc(clampk(C::STAGES)), xr_b = x_desc(clampk(C::STAGES));
+    // descriptors of the fill that is half way (step kt+S-1) and of the one that starts in G2 (step kt+S)
+    __amdgpu_buffer_rsrc_t wr_a = w_desc(C::STAGES - 1), xr_a = x_desc(C::STAGES - 1);
+    __amdgpu_buffer_rsrc_t wr_b = w_desc(C::STAGES), xr_b = x_desc(C::STAGES);
     fill_quarter(wr_a, xr_a, C::STAGES - 1, 0);
     fill_quarter(wr_a, xr_a, C::STAGES - 1, 1);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(C::LOADS * (C::STAGES - 2) + C::HALF_LOADS));   // tile 0 is in
@@ -242,7 +254,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     __builtin_amdgcn_sched_barrier(0);
 
     int stage = 0;      // ring position of tile kt
-    for (int kt = 0; kt < ktiles; ++kt) {
+    for (int kt = 0; kt < steps; ++kt) {
         const int stage_next = stage + 1 == C::STAGES ? 0 : stage + 1;
         const int stage_prev = stage == 0 ? C::STAGES - 1 : stage - 1;   // holds tile kt+S-1 (being filled)
         // G0
@@ -268,15 +280,47 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         fill_quarter(wr_b, xr_b, stage, 1);
         wr_a = wr_b;
         xr_a = xr_b;
-        wr_b = w_desc(clampk(kt + C::STAGES + 1));
-        xr_b = x_desc(clampk(kt + C::STAGES + 1));
+        wr_b = w_desc(kt + C::STAGES + 1);
+        xr_b = x_desc(kt + C::STAGES + 1);
         group(opW[1], opX[1], opW[0], opX[0], rawW[0], rawX[0], 0);
         pin(false, 1);
         stage = stage_next;
     }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the repeated tail loads before LDS is reused
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the tail loads before LDS is reused
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
     __builtin_amdgcn_s_barrier();
+
+    // ---- K groups: groups 1.. hand their accumulators to group 0 through LDS (integers: exact, order-free),
+    // one group at a time, register-major so that every access is a run of consecutive words; then they leave
+    // (nothing below synchronises across waves).
+    if (C::KS > 1) {
+        int32_t *red = reinterpret_cast<int32_t *>(lds) + wave * 64 + lane;
+        constexpr int RSTRIDE = C::WAVES * 64;
+#pragma unroll 1
+        for (int g = 1; g < C::KS; ++g) {
+            if (kg == g) {
+#pragma unroll
+                for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+                    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) red[((tn * C::TM + tm) * 16 + r) * RSTRIDE] = acc[tn][tm][r];
+            }
+            __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+            __builtin_amdgcn_s_barrier();
+            if (kg == 0) {
+#pragma unroll
+                for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+                    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[tn][tm][r] += red[((tn * C::TM + tm) * 16 + r) * RSTRIDE];
+            }
+            __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+            __builtin_amdgcn_s_barrier();
+        }
+        if (kg != 0) return;
+    }
 
     // ---- epilogue.  W was the A operand, so an accumulator tile is [n][m]: a lane owns token
     // m = lane % 32 and, per register quad q, four consecutive output channels
@@ -409,13 +453,14 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     if (K > 131071 || (wsum && K > 65535) || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     // Tile shapes (all 4 waves).  The 256 x 256 tile has the best operand reuse and wins for long K;
     // 256 x 128 with two workgroups per CU hides prologue and epilogue and fills partial rounds, and
-    // wins elsewhere; the 192- and one-workgroup 128-row shapes are kept for shapes neither fits; 128 x 128
-    // serves problems with very few output tiles.
+    // wins elsewhere; the 192- and one-workgroup 128-row shapes are kept for shapes neither fits; the
+    // two-K-group shapes serve problems with at most one workgroup per CU.
     typedef GemmCfg<2, 2, 4, 4, 4> T256x256;   // waves of 128 x 128
     typedef GemmCfg<2, 2, 3, 4, 4> T192x256;   // BN = 192: waves of 96 (n) x 128 (m)
     typedef GemmCfg<2, 2, 4, 2, 4> T256x128;   // BM = 128: waves of 128 (n) x 64 (m)
     typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;   // the same tile, two workgroups per CU
-    typedef GemmCfg<2, 2, 2, 2, 3, 3> T128x128o3;   // waves of 64 x 64, three workgroups per CU
+    typedef GemmCfg<2, 2, 2, 2, 3, 1, 2> T128x128k2;   // 128 x 128 alone on a CU, two K groups
+    typedef GemmCfg<2, 2, 4, 2, 3, 1, 2> T256x128k2;   // 256 x 128 alone on a CU, two K groups
     // Estimated time in microseconds, fitted to measurements on uniform random operands (the clock is
     // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
     // one-workgroup-per-CU shapes run ceil(tiles / 256) rounds of (fixed + per-K-tile) each.  With two
@@ -435,15 +480,19 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     if (g_forced_tile <= 0) {
         for (int i = 1; i < 4; ++i)
             if (cost[i] < cost[pick]) pick = i;
-        // Problems so small that even 128 x 128 tiles give every CU at most one workgroup: the kernel time is
-        // one workgroup's walk through K, and the small tile walks fastest (measured 19 against 25 us at
-        // K = 4096).  A deeper ring does not help there; filling the idle CUs would take a split of K.
+        // At most one workgroup per CU: one wave per SIMD cannot hide its own latencies, so the tile gets a
+        // second K group (measured 69 against 72 us on the c2 down projection).  Problems so small that even
+        // 128 x 128 tiles give every CU at most one workgroup take that tile: the kernel time is then one
+        // workgroup's walk through K and the small tile walks fastest (17 against 25 us at K = 4096).  A deeper
+        // ring does not help there; filling the idle CUs would take a split of K across workgroups.
+        if (pick == 2 && tiles(256, 128) <= CUS) pick = 5;
         if (tiles(128, 128) <= CUS) pick = 4;
     }
     if (pick == 1) return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 2) return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 4) return launch_cfg<T128x128o3>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 4) return launch_cfg<T128x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 5) return launch_cfg<T256x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 
