@@ -61,6 +61,19 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) xp[mt] = xq + (int64_t)min(mt * 16 + fi, M - 1) * SEG + fg * 16;
 
+    // Scales of the first output this thread will write (for up to 16 tokens: its only one), fetched now so
+    // that the epilogue of this short kernel does not end on a memory round trip.
+    float cw0 = 0.0f, d0 = 1.0f;
+    int32_t zw0 = 0;
+    if (tid < RT * MT * 256) {
+        const int g = tid >> 8, n = n0 + (g / MT) * 16 + (tid & 15), t = (g % MT) * 16 + ((tid >> 4) & 15);
+        if (n < N) {
+            cw0 = s_a * s_w[n];
+            if (wsum) zw0 = zp * wsum[n];
+        }
+        if (d && t < M) d0 = d[t];
+    }
+
     const int T = wave < ktiles ? (ktiles - wave + WAVES - 1) / WAVES : 0;   // K tiles of this wave
     v4i acc[RT][MT];
 #pragma unroll
@@ -120,8 +133,14 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
         const int32_t sum = red[g * 256 + (i & 3) * 64 + 4 * j + (i >> 2)];
         const int t = mt * 16 + j, n = n0 + rt * 16 + i;
         if (t < M && n < N) {
+            const bool first = o == tid;
             const int32_t a = sum >> 8;                // exact: the sum is 256 * acc
-            y[(int64_t)t * N + n] = dequant_bf16(remove_zero_point(a, zp, wsum, n), s_a * s_w[n], d, t);
+            // y = bf16((float)(acc - z * wsum[n]) * (s_a * s_w[n]) [* d_t]): fp32 throughout, no fused operations
+            const float cw = first ? cw0 : s_a * s_w[n];
+            const int32_t zw = wsum ? (first ? zw0 : zp * wsum[n]) : 0;
+            float yf = (float)(a - zw) * cw;
+            if (d) yf = yf * (first ? d0 : d[t]);
+            y[(int64_t)t * N + n] = bf16_rne(yf);
             if (acc_out) acc_out[(int64_t)t * N + n] = a;
         }
     }
