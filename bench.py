@@ -196,6 +196,9 @@ def main():
     # ------------------------------------------------------------------ activation-side kernels and the widened rows
     out["activation_kernels"] = activation_summary(torch, fptq, dev, x_gu, x_dn, r_dn, s_gu, s_dn, gate, down, layers, xq_dn, ys)
 
+    # ------------------------------------------------------------------ few output tiles: the split over K with a workspace
+    out["few_tile_linear"] = few_tile_summary(torch, fptq, dev)
+
     # ------------------------------------------------------------------ decode summary (config c4)
     if not args.no_decode:
         out["decode"] = decode_summary(torch, fptq, dev)
@@ -275,6 +278,22 @@ def attainable_summary(torch, fptq, dev):
     torch.cuda.synchronize()
     res["stream_read_1GiB_GBps"] = round(5 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
     return res
+
+
+def few_tile_summary(torch, fptq, dev):
+    """Llama-3-8B down projection (N = 4096, K = 14336) at 256 tokens: 64 output tiles for 256 CUs.  fptq_w4a4_linear
+    against fptq_w4a4_linear_ws, which splits K over four workgroups per tile through a caller workspace."""
+    M, N, K = 256, 4096, 14336
+    xq = torch.randint(0, 256, (fptq.fptq_packed_bytes(M, K),), dtype=torch.uint8, device=dev)
+    wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(N, K),), dtype=torch.uint8, device=dev)
+    s_w = torch.rand(N, device=dev) * 0.015 + 0.005
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    ws = torch.zeros(fptq.fptq_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=dev)
+    plain = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.5, s_w, out=y), iters=10, replays=3)
+    split = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, 0.5, s_w, ws, out=y), iters=10, replays=3)
+    ops = 2 * M * N * K
+    return {"shape": "M 256 x N 4096 x K 14336", "plain_us": round(plain, 1), "plain_TOPS": round(ops / plain / 1e6, 1),
+            "workspace_us": round(split, 1), "workspace_TOPS": round(ops / split / 1e6, 1), "workspace_MiB": ws.numel() >> 20}
 
 
 def graph_time_us(torch, fn, iters=20, replays=5):

@@ -167,6 +167,23 @@ int fptq_w4a4_linear_zp(const void *xq_packed, const void *w_packed, int64_t M, 
                         const float *s_w, const float *row_out_scale, int zero_point, const int32_t *w_row_sum,
                         void *y_bf16, int32_t *acc_dbg, void *stream);
 
+/*
+ * fptq_w4a4_linear with a workspace.  Between about 129 and 1024 tokens a matrix with few output channels
+ * gives the prefill kernel fewer output tiles than the device has CUs; with a workspace the kernel splits K
+ * over several workgroups per tile, which leave their partial INT32 accumulators in the workspace, and the
+ * last one to arrive adds them (integers: the result does not depend on the order) and writes y.
+ *   workspace        device, 256-byte aligned, at least fptq_linear_workspace_bytes(M, N, K) bytes, or NULL.
+ *                    It must be zero-filled once before its first use; every call leaves the part that has
+ *                    to be zero as it found it.  Calls that share a workspace must not overlap in time.
+ *   workspace_bytes  its size.  Too small, NULL, or a shape that does not profit (fptq_linear_workspace_bytes
+ *                    returns 0): the call behaves exactly like fptq_w4a4_linear.
+ * Results are identical to fptq_w4a4_linear's.
+ */
+int64_t fptq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int fptq_w4a4_linear_ws(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                        const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *workspace,
+                        int64_t workspace_bytes, void *stream);
+
 /* Same contract as fptq_w4a4_linear but always runs the simple one-thread-per-output kernel
  * (no MFMA, no LDS).  A second, independent GPU implementation used by the tests to cross-check
  * the tuned kernels at full size. */

@@ -20,7 +20,7 @@ EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_we
            "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic", "fptq_quantize_act_asym",
            "fptq_weight_row_sums", "fptq_w4a4_linear_zp", "fptq_residual_norm_quantize",
            "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile",
-           "fptq_probe_mfma_rate", "fptq_probe_read"]
+           "fptq_probe_mfma_rate", "fptq_probe_read", "fptq_linear_workspace_bytes", "fptq_w4a4_linear_ws"]
 
 _lib = None
 
@@ -67,6 +67,10 @@ def lib():
         L.fptq_set_gemm_tile.argtypes = [i32]
         L.fptq_unpack.restype = i32
         L.fptq_unpack.argtypes = [p, i64, i64, p, p]
+        L.fptq_linear_workspace_bytes.restype = i64
+        L.fptq_linear_workspace_bytes.argtypes = [i64, i64, i64]
+        L.fptq_w4a4_linear_ws.restype = i32
+        L.fptq_w4a4_linear_ws.argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p, i64, p]
         L.fptq_probe_mfma_rate.restype = i64
         L.fptq_probe_mfma_rate.argtypes = [i32, i32, p, p]
         L.fptq_probe_read.restype = i32
@@ -224,6 +228,23 @@ def _linear(fn, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc):
 def fptq_w4a4_linear(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None, want_acc=False, acc=None):
     """Packed activations x packed weights -> bf16 [M, N] (and the int32 accumulators if asked)."""
     return _linear(lib().fptq_w4a4_linear, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc)
+
+
+def fptq_linear_workspace_bytes(M, N, K):
+    """Bytes of workspace fptq_w4a4_linear_ws would use for this shape (0: it would not use one)."""
+    n = lib().fptq_linear_workspace_bytes(M, N, K)
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def fptq_w4a4_linear_ws(xq, wq, M, N, K, s_a, s_w, workspace, row_out_scale=None, out=None, want_acc=False, acc=None):
+    """fptq_w4a4_linear with a zero-initialised uint8 device workspace (or None) for the split over K."""
+    if workspace is not None:
+        _dev(workspace, torch.uint8, "workspace")
+    fn = lambda a, b, m, n, k, sa, sw, d, y, ac, st: lib().fptq_w4a4_linear_ws(
+        a, b, m, n, k, sa, sw, d, y, ac, _ptr(workspace), 0 if workspace is None else workspace.numel(), st)
+    return _linear(fn, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc)
 
 
 def fptq_w4a4_linear_ref(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None, want_acc=False, acc=None):

@@ -54,7 +54,7 @@ typedef hipError_t (*linear_fn)(const uint8_t *, const uint8_t *, int64_t, int64
 
 static int linear_common(const char *fn, linear_fn force, const void *xq, const void *wq, int64_t M, int64_t N,
                          int64_t K, float s_a, const float *s_w, const float *d, int zp, const int32_t *wsum, void *y,
-                         int32_t *acc, void *stream)
+                         int32_t *acc, void *stream, void *workspace = nullptr, int64_t workspace_bytes = 0)
 {
     if (!xq || !wq || !s_w || !y) {
         set_error("%s: NULL pointer", fn);
@@ -78,9 +78,18 @@ static int linear_common(const char *fn, linear_fn force, const void *xq, const 
         return FPTQ_ERR_VALUE;
     }
     if (zp == 0) wsum = nullptr;
+    if ((rc = check_align(fn, workspace, 256, "workspace"))) return rc;
+    if (workspace_bytes < 0) {
+        set_error("%s: negative workspace_bytes", fn);
+        return FPTQ_ERR_SIZE;
+    }
     linear_fn f = force ? force : (few_token_shape(M, N) && forced_gemm_tile() == 0 ? launch_linear_decode : launch_linear_mfma);
-    hipError_t e = f((const uint8_t *)xq, (const uint8_t *)wq, M, N, K, s_a, s_w, d, zp, wsum, (uint16_t *)y, acc,
-                     (hipStream_t)stream);
+    hipError_t e;
+    if (f == launch_linear_mfma && workspace)
+        e = launch_linear_mfma_ws((const uint8_t *)xq, (const uint8_t *)wq, M, N, K, s_a, s_w, d, zp, wsum, (uint16_t *)y, acc,
+                                  (int32_t *)workspace, workspace_bytes, (hipStream_t)stream);
+    else
+        e = f((const uint8_t *)xq, (const uint8_t *)wq, M, N, K, s_a, s_w, d, zp, wsum, (uint16_t *)y, acc, (hipStream_t)stream);
     return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
 }
 
@@ -274,6 +283,23 @@ int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M,
 {
     return linear_common("fptq_w4a4_linear_ref", launch_linear_ref, xq_packed, w_packed, M, N, K, s_a, s_w,
                          row_out_scale, 0, nullptr, y_bf16, acc_dbg, stream);
+}
+
+int64_t fptq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    const char *fn = "fptq_linear_workspace_bytes";
+    int rc;
+    if ((rc = check_dims(fn, M, K, "M", "K")) || (rc = check_dims(fn, N, K, "N", "K")) || (rc = check_dims(fn, M, N, "M", "N")))
+        return rc;
+    return few_token_shape(M, N) ? 0 : linear_workspace_bytes(M, N, K);
+}
+
+int fptq_w4a4_linear_ws(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                        const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *workspace,
+                        int64_t workspace_bytes, void *stream)
+{
+    return linear_common("fptq_w4a4_linear_ws", nullptr, xq_packed, w_packed, M, N, K, s_a, s_w, row_out_scale, 0, nullptr, y_bf16,
+                         acc_dbg, stream, workspace, workspace_bytes);
 }
 
 int fptq_set_gemm_tile(int tile)

@@ -38,6 +38,10 @@ hipError_t launch_linear_ref(const uint8_t *xq, const uint8_t *wq, int64_t M, in
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                               const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                               hipStream_t s);
+hipError_t launch_linear_mfma_ws(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                                 const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                                 int32_t *ws, int64_t ws_bytes, hipStream_t s);
+int64_t linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
 hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                                 const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                                 hipStream_t s);

@@ -32,14 +32,20 @@ constexpr int WAIT_LGKM0 = 15 | (3 << 14) | (7 << 4) | (0 << 8);
 // raw buffer descriptor, dword 3: 32-bit data format, no swizzle (gfx9 family encoding)
 constexpr int RSRC_FLAGS = 0x00020000;
 
+constexpr int MAX_SPLITS = 4;     // K ranges per output tile in the split-K variant
+
 // OCC_ = workgroups meant to share a CU (caps the register budget: 512 / OCC_ per lane).  KS_ = K groups:
 // KS_ sets of WAVES waves work on the same output tile, set g on K tiles g, g + KS_, ..., each with its own
 // LDS ring; their accumulators are added through LDS before the epilogue.  A problem with at most one
 // workgroup per CU runs one wave per SIMD, which cannot hide its own LDS and VALU latencies; a second K group
 // gives every SIMD a second wave without needing more output tiles.
-template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_, int OCC_ = 1, int KS_ = 1>
+// SPLIT_: several workgroups share an output tile, each on a contiguous range of K tiles; they leave their
+// partial accumulators in a caller-provided workspace and the last one to arrive adds them and runs the epilogue.
+template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_, int OCC_ = 1, int KS_ = 1, bool SPLIT_ = false>
 struct GemmCfg {
     static constexpr int WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, TN = TN_, TM = TM_, STAGES = STAGES_, OCC = OCC_, KS = KS_;
+    static constexpr bool SPLIT = SPLIT_;
+    static constexpr int ACC_REGS = TN_ * TM_ * 16;             // accumulator registers of a lane
     static constexpr int BN = WAVES_N * TN * 32, BM = WAVES_M * TM * 32;
     static constexpr int WAVES = WAVES_N * WAVES_M, THREADS = 64 * WAVES * KS;
     static constexpr int W_BYTES = BN * SEG, X_BYTES = BM * SEG, STAGE_BYTES = W_BYTES + X_BYTES;
@@ -90,7 +96,7 @@ template <class C, bool ALIGNED, bool DUMP>
 __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, int tiles_m,
     int tiles_n, float s_a, const float *__restrict__ s_w, const float *__restrict__ d, int zp,
-    const int32_t *__restrict__ wsum, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out)
+    const int32_t *__restrict__ wsum, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out, int32_t *ws, int splits)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -103,7 +109,11 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     // contiguous run of logical tiles so that its L2 sees neighbouring tiles, then walk the tile grid
     // in bands of 8 N-tiles with M fastest, so that concurrent tiles share X and W panels.
     const int total = tiles_m * tiles_n;
-    int pid = blockIdx.x;
+    int pid = blockIdx.x, split = 0;
+    if (C::SPLIT) {                                  // workgroup = (split, tile), tiles fastest
+        split = pid / total;
+        pid -= split * total;
+    }
     {
         const int per = (total + 7) / 8, tall = total % 8 == 0 ? 8 : total % 8;
         const int xcd = pid % 8, local = pid / 8;
@@ -131,16 +141,22 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const int64_t w_slab = (int64_t)N * SEG, x_slab = (int64_t)M * SEG;   // bytes per K tile of all rows
 
     // per-slab descriptors: rows past N (M) fail the bounds check and read as zero.  Step j of this K group
-    // is K tile j * KS + kg; a step past the last tile gets an empty descriptor, so its loads are still
+    // is K tile kt_begin + j * KS + kg; a step past the last tile gets an empty descriptor, so its loads are still
     // issued (the outstanding-load count stays uniform) but read nothing and land as zeros.
+    int kt_begin = 0, kt_end = ktiles;               // K tiles of this workgroup
+    if (C::SPLIT) {
+        const int per = (ktiles + splits - 1) / splits;
+        kt_begin = split * per;
+        kt_end = min(ktiles, kt_begin + per);
+    }
     auto w_desc = [&](int j) {
-        const int kt = j * C::KS + kg;
-        const bool in = kt < ktiles;
+        const int kt = kt_begin + j * C::KS + kg;
+        const bool in = kt < kt_end;
         return __builtin_amdgcn_make_buffer_rsrc((void *)(wq + (in ? kt : 0) * w_slab), 0, in ? (int)w_slab : 0, RSRC_FLAGS);
     };
     auto x_desc = [&](int j) {
-        const int kt = j * C::KS + kg;
-        const bool in = kt < ktiles;
+        const int kt = kt_begin + j * C::KS + kg;
+        const bool in = kt < kt_end;
         return __builtin_amdgcn_make_buffer_rsrc((void *)(xq + (in ? kt : 0) * x_slab), 0, in ? (int)x_slab : 0, RSRC_FLAGS);
     };
     // quarter q (0..3) of the fill of one K tile: W chunk q and X chunk q, where they exist
@@ -232,7 +248,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int steps = (ktiles + C::KS - 1) / C::KS;      // the same for every K group: they share the barriers
+    const int steps = (max(kt_end - kt_begin, 0) + C::KS - 1) / C::KS;      // the same for every K group: they share the barriers
 #pragma unroll
     for (int s = 0; s < C::STAGES - 1; ++s) {
         __amdgpu_buffer_rsrc_t wr = w_desc(s), xr = x_desc(s);
@@ -319,6 +335,68 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
             __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
             __builtin_amdgcn_s_barrier();
         }
+        if (!C::SPLIT && kg != 0) return;
+    }
+
+    // ---- split K: leave the partial tile in the workspace, count the arrival, and let the last workgroup of
+    // the tile add the others' partials and go on to the epilogue.  Nobody waits for anybody, so there is nothing
+    // to hang on.  The workgroups of a tile run on different XCDs, whose L2s are not coherent with each other, and
+    // a device-wide fence would write back and invalidate a whole L2 per workgroup; instead the partials are
+    // stored and loaded with the device-coherent cache policy (sc0 sc1: written through to, and read from, the
+    // memory side), the stores are complete (vmcnt) before the arrival is counted, and the count is an atomic
+    // at the same scope.  Workspace: [total] arrival counters (zero between calls), then
+    // [splits][total][ACC_REGS / 4][threads of a K group] partials as 16-byte quads, lane-contiguous.
+    if (C::SPLIT) {
+        constexpr int TPG = C::WAVES * 64, QUADS = C::ACC_REGS / 4, COHERENT = 1 | 16;     // aux bits: sc0, sc1
+        const int64_t slice = (int64_t)C::ACC_REGS * TPG;
+        int32_t *counters = ws, *parts = ws + ((total + 63) & ~63);
+        int *flag = reinterpret_cast<int *>(lds + C::LDS_BYTES - 16);     // clear of the reduction and epilogue regions
+        const int qoff = (wave * 64 + lane) * 16;
+        if (kg == 0) {
+            const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(parts + ((int64_t)split * total + pid) * slice), 0, (int)slice * 4, RSRC_FLAGS);
+#pragma unroll
+            for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4i v = {acc[tn][tm][4 * q], acc[tn][tm][4 * q + 1], acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(v, mine, qoff + ((tn * C::TM + tm) * 4 + q) * (TPG * 16), 0, COHERENT);
+                    }
+            static_assert(QUADS == C::TN * C::TM * 4, "quads per lane");
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // this wave's partials have reached the memory side
+        __syncthreads();
+        if (tid == 0) *flag = __hip_atomic_fetch_add(counters + pid, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*flag != splits - 1) return;             // the whole workgroup: not the last one of this tile
+        if (kg == 0) {
+            // the other (at most MAX_SPLITS - 1) partial tiles, read side by side so that their latencies overlap
+            __amdgpu_buffer_rsrc_t other[MAX_SPLITS - 1];
+#pragma unroll
+            for (int j = 0; j < MAX_SPLITS - 1; ++j) {
+                const int s2 = (split + 1 + j) % splits;            // j < splits - 1: every other split once
+                other[j] = __builtin_amdgcn_make_buffer_rsrc((void *)(parts + ((int64_t)s2 * total + pid) * slice), 0,
+                                                             j < splits - 1 ? (int)slice * 4 : 0, RSRC_FLAGS);
+            }
+#pragma unroll
+            for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        v4i v[MAX_SPLITS - 1];
+#pragma unroll
+                        for (int j = 0; j < MAX_SPLITS - 1; ++j)      // an empty descriptor (j >= splits - 1) reads zeros
+                            v[j] = __builtin_amdgcn_raw_buffer_load_b128(other[j], qoff + ((tn * C::TM + tm) * 4 + q) * (TPG * 16), 0, COHERENT);
+#pragma unroll
+                        for (int j = 0; j < MAX_SPLITS - 1; ++j)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[tn][tm][4 * q + e] += v[j][e];
+                    }
+        }
+        if (tid == 0) counters[pid] = 0;             // as it was found, for the next call
         if (kg != 0) return;
     }
 
@@ -415,7 +493,7 @@ int forced_gemm_tile() { return g_forced_tile; }
 template <class C, bool ALIGNED, bool DUMP>
 static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                               const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
-                              hipStream_t s)
+                              hipStream_t s, int32_t *ws = nullptr, int splits = 1)
 {
     static bool attr_set = false;
     auto kern = linear_mfma_kernel<C, ALIGNED, DUMP>;
@@ -425,22 +503,62 @@ static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, i
         attr_set = true;
     }
     int64_t tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
-    if (tiles_m * tiles_n > 0x7fffffff) return hipErrorInvalidValue;
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(C::THREADS), C::LDS_BYTES, s>>>(
-        xq, wq, (int)M, (int)N, (int)k_tiles(K), (int)tiles_m, (int)tiles_n, s_a, s_w, d, zp, wsum, y, acc);
+    if (tiles_m * tiles_n * splits > 0x7fffffff) return hipErrorInvalidValue;
+    kern<<<dim3((unsigned)(tiles_m * tiles_n * splits)), dim3(C::THREADS), C::LDS_BYTES, s>>>(
+        xq, wq, (int)M, (int)N, (int)k_tiles(K), (int)tiles_m, (int)tiles_n, s_a, s_w, d, zp, wsum, y, acc, ws, splits);
     return hipGetLastError();
 }
 
 template <class C>
 static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
-                              hipStream_t s)
+                             hipStream_t s, int32_t *ws = nullptr, int splits = 1)
 {
     const bool aligned = N % 8 == 0;
-    if (acc) return aligned ? launch_inst<C, true, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
-                            : launch_inst<C, false, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    return aligned ? launch_inst<C, true, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
-                   : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (acc) return aligned ? launch_inst<C, true, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits)
+                            : launch_inst<C, false, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits);
+    return aligned ? launch_inst<C, true, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits)
+                   : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits);
+}
+
+// ---- split K over workgroups, for problems whose 128 x 128 tiles cover less than half of the CUs.
+typedef GemmCfg<2, 2, 2, 2, 3, 1, 2, true> T128x128k2split;
+
+// Number of K ranges: as many as keep the workgroup count within the CUs, at most MAX_SPLITS, at least 16 K tiles
+// each, none empty.  The exchange of partials costs about as much as 16 K tiles of work, so only long K is split
+// (measured on N = 4096, M = 256: K = 14336 goes from 44 to 34 us, K = 4096 would go from 17 to 19).
+static int split_count(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t tiles = ((N + 127) / 128) * ((M + 127) / 128), kt = k_tiles(K);
+    if (tiles > 128 || K > 131071 || kt < 64) return 1;
+    int64_t sp = 256 / tiles;
+    if (sp > kt / 16) sp = kt / 16;
+    if (sp > MAX_SPLITS) sp = MAX_SPLITS;
+    if (sp < 2) return 1;
+    const int64_t per = (kt + sp - 1) / sp;
+    return (int)((kt + per - 1) / per);
+}
+
+int64_t linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    const int sp = split_count(M, N, K);
+    if (sp < 2) return 0;
+    const int64_t tiles = ((N + 127) / 128) * ((M + 127) / 128);
+    return (((tiles + 63) & ~(int64_t)63) + sp * tiles * T128x128k2split::ACC_REGS * (T128x128k2split::WAVES * 64)) * 4;
+}
+
+hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                              hipStream_t s);
+
+hipError_t launch_linear_mfma_ws(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                                 const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                                 int32_t *ws, int64_t ws_bytes, hipStream_t s)
+{
+    const int sp = split_count(M, N, K);
+    if (sp < 2 || !ws || ws_bytes < linear_workspace_bytes(M, N, K) || (wsum && K > 65535) || forced_gemm_tile() != 0)
+        return launch_linear_mfma(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    return launch_cfg<T128x128k2split>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, sp);
 }
 
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
