@@ -68,6 +68,25 @@ def test_split_equals_unsplit_at_size(M, N, K):
     assert torch.equal(y0.view(torch.int16), y2.view(torch.int16))
 
 
+def test_split_never_reads_a_previous_call_s_partials():
+    """The same workspace under alternating inputs: a partial tile left over from the previous call (a stale cache
+    line on another XCD, say) would show up as a wrong sum."""
+    M, N, K = 256, 4096, 14336
+    torch.manual_seed(5)
+    wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(N, K),), dtype=torch.uint8, device="cuda")
+    s_w = torch.rand(N, device="cuda") * 0.015 + 0.005
+    xs = [torch.randint(0, 256, (fptq.fptq_packed_bytes(M, K),), dtype=torch.uint8, device="cuda") for _ in range(3)]
+    want = [fptq.fptq_w4a4_linear(x, wq, M, N, K, 0.5, s_w, want_acc=True)[1] for x in xs]
+    _, ws = zero_ws(M, N, K)
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    bad = 0
+    for it in range(150):
+        i = it % 3
+        fptq.fptq_w4a4_linear_ws(xs[i], wq, M, N, K, 0.5, s_w, ws, acc=acc)
+        bad += int((acc != want[i]).sum())
+    assert bad == 0
+
+
 def test_workspace_too_small_or_absent_falls_back():
     M, N, K = 256, 1024, 8192
     torch.manual_seed(1)
