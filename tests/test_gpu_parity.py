@@ -161,6 +161,24 @@ def test_linear_worst_case_accumulator(oracle):
     assert torch.all(acc == -56 * K)
 
 
+@pytest.mark.parametrize("M", [3, 200])
+def test_k_beyond_the_widened_accumulator_limit(oracle, M):
+    """K > 131071: 256 * acc no longer fits int32, so both tuned kernels hand over to the simple one.  All operands
+    -8: the largest accumulator there is."""
+    N, K = 40, 131072 + 192
+    x = np.full((M, K), -8, np.int8)
+    w = np.full((N, K), -8, np.int8)
+    rng = np.random.default_rng(M)
+    w[::3] = rng.integers(-8, 8, (len(w[::3]), K), dtype=np.int8)
+    s_w = rng.uniform(0.005, 0.02, N).astype(np.float32)
+    xq, wq = fptq.fptq_pack_weights(dev(x)), fptq.fptq_pack_weights(dev(w))
+    y, acc = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.25, dev(s_w), want_acc=True)
+    acc_ref = oracle.gemm_i64(x, w)
+    assert acc_ref.max() == 64 * K
+    assert np.array_equal(acc.cpu().numpy(), acc_ref.astype(np.int32))
+    assert np.array_equal(host_bits(y), oracle.epilogue(acc_ref.astype(np.int32), np.float32(0.25), s_w))
+
+
 def test_linear_is_deterministic():
     inp = synth.draw(small_case(300, 520, 2048, synth.MODE_RMS, seed=5))
     a = run_gpu_linear(inp)
