@@ -35,6 +35,24 @@ def test_asymmetric_quantizer_every_bf16_pattern(oracle, zp, s_a):
     assert np.array_equal(q, oracle.quantize_zp(allbits, np.float32(s_a), zp, r))
 
 
+@pytest.mark.parametrize("M", [5, 200])
+def test_asymmetric_linear_long_k(oracle, M):
+    """K > 65535 with a zero point: the staged correction 256 * z * wsum of the MFMA kernel could overflow, so that
+    kernel hands over to the simple one; extreme operands (all codes -8, zero point -8, weights -8)."""
+    N, K, zp = 24, 65536 + 320, -8
+    q = np.full((M, K), -8, np.int8)
+    w = np.full((N, K), -8, np.int8)
+    rng = np.random.default_rng(M)
+    w[1::2] = rng.integers(-8, 8, (len(w[1::2]), K), dtype=np.int8)
+    s_w = rng.uniform(0.005, 0.02, N).astype(np.float32)
+    wsum = fptq.fptq_weight_row_sums(dev(w))
+    y, acc = fptq.fptq_w4a4_linear_zp(fptq.fptq_pack_weights(dev(q)), fptq.fptq_pack_weights(dev(w)), M, N, K, 0.125, dev(s_w), zp,
+                                      wsum, want_acc=True)
+    acc_ref = oracle.gemm_i64(q, w).astype(np.int32)
+    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    assert np.array_equal(host_bits(y), oracle.epilogue_zp(acc_ref, np.float32(0.125), s_w, zp, oracle.weight_row_sums(w)))
+
+
 def test_weight_row_sums(oracle):
     rng = np.random.default_rng(0)
     for N, K in [(1, 1), (5, 34), (300, 4096), (64, 11008)]:
