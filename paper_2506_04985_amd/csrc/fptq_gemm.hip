@@ -270,6 +270,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     __builtin_amdgcn_sched_barrier(0);
 
     int stage = 0;      // ring position of tile kt
+    __builtin_amdgcn_s_setprio(2);     // MFMA loop: ahead of other workgroups' prologues and epilogues on this SIMD
     for (int kt = 0; kt < steps; ++kt) {
         const int stage_next = stage + 1 == C::STAGES ? 0 : stage + 1;
         const int stage_prev = stage == 0 ? C::STAGES - 1 : stage - 1;   // holds tile kt+S-1 (being filled)
@@ -302,6 +303,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         pin(false, 1);
         stage = stage_next;
     }
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // drain the tail loads before LDS is reused
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
     __builtin_amdgcn_s_barrier();
