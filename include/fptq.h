@@ -193,8 +193,8 @@ int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M,
 /* Testing / tuning knob for the prefill kernel's tile shape (process-wide, not thread-safe against
  * concurrent fptq_w4a4_linear calls): 0 = chosen per problem (default), 1 = 256x256, 2 = 192 (N) x
  * 256 (M), 3 = 256 (N) x 128 (M), 4 = 256 x 128 with two workgroups per CU, 5 = 128 x 128 and
- * 6 = 256 x 128 with two K groups per workgroup.  A forced shape also sends calls with few tokens to
- * the prefill kernel.  Results do not depend on it. */
+ * 6 = 256 x 128 with two K groups per workgroup, 7 = 64 x 64 and 8 = 128 (N) x 64 (M) with two K groups.
+ * A forced shape also sends calls with few tokens to the prefill kernel.  Results do not depend on it. */
 int fptq_set_gemm_tile(int tile);
 
 /*

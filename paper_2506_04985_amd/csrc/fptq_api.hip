@@ -304,8 +304,8 @@ int fptq_w4a4_linear_ws(const void *xq_packed, const void *w_packed, int64_t M, 
 
 int fptq_set_gemm_tile(int tile)
 {
-    if (tile < 0 || tile > 6) {
-        set_error("fptq_set_gemm_tile: tile must be 0..6");
+    if (tile < 0 || tile > 8) {
+        set_error("fptq_set_gemm_tile: tile must be 0..8");
         return FPTQ_ERR_VALUE;
     }
     set_gemm_tile(tile);

@@ -224,9 +224,9 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         for (int i = 0; i < NM; ++i) {
             const int tn = i / C::TM, tm = i % C::TM;
             acc[tn][tm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cw[tn], cx[tm], acc[tn][tm], 0, 0, 0);
-            if ((i * NOP) / NM != ((i + 1) * NOP) / NM) {      // spread the NOP widenings over the NM MFMAs
-                const int o = (i * NOP) / NM;                 // order: W0, X0..X(TM-1), W1..W(TN-1)
-                if (o == 0) nw[0] = widen(rw[0][2 * h], rw[0][2 * h + 1]);
+#pragma unroll
+            for (int o = (i * NOP) / NM; o < ((i + 1) * NOP) / NM; ++o) {   // spread the NOP widenings over the NM MFMAs
+                if (o == 0) nw[0] = widen(rw[0][2 * h], rw[0][2 * h + 1]);    // order: W0, X0..X(TM-1), W1..W(TN-1)
                 else if (o <= C::TM) nx[o - 1] = widen(rx[o - 1][2 * h], rx[o - 1][2 * h + 1]);
                 else nw[o - C::TM] = widen(rw[o - C::TM][2 * h], rw[o - C::TM][2 * h + 1]);
             }
@@ -241,7 +241,10 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (reads && (i * NOP) / NM != ((i + 1) * NOP) / NM) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (reads) {
+#pragma unroll
+                for (int o = (i * NOP) / NM; o < ((i + 1) * NOP) / NM; ++o) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
             if ((i == NM / 4 && n_vmem > 0) || (i == (3 * NM) / 4 && n_vmem > 1)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
         }
@@ -527,12 +530,13 @@ static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, in
 typedef GemmCfg<2, 2, 2, 2, 3, 1, 2, true> T128x128k2split;
 
 // Number of K ranges: as many as keep the workgroup count within the CUs, at most MAX_SPLITS, at least 16 K tiles
-// each, none empty.  The exchange of partials costs about as much as 16 K tiles of work, so only long K is split
-// (measured on N = 4096, M = 256: K = 14336 goes from 44 to 34 us, K = 4096 would go from 17 to 19).
+// each, none empty.  The exchange of partials costs about as much as 16 K tiles of work and the unsplit kernel has
+// small tiles for such problems, so only long K is split (measured on N = 4096, M = 256: K = 14336 takes 31 us
+// unsplit and 25 split, K = 8192 18 and 19.5).
 static int split_count(int64_t M, int64_t N, int64_t K)
 {
     const int64_t tiles = ((N + 127) / 128) * ((M + 127) / 128), kt = k_tiles(K);
-    if (tiles > 128 || K > 131071 || kt < 64) return 1;
+    if (tiles > 128 || K > 131071 || kt < 96) return 1;
     int64_t sp = 256 / tiles;
     if (sp > kt / 16) sp = kt / 16;
     if (sp > MAX_SPLITS) sp = MAX_SPLITS;
@@ -581,6 +585,8 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;   // the same tile, two workgroups per CU
     typedef GemmCfg<2, 2, 2, 2, 3, 1, 2> T128x128k2;   // 128 x 128 alone on a CU, two K groups
     typedef GemmCfg<2, 2, 4, 2, 3, 1, 2> T256x128k2;   // 256 x 128 alone on a CU, two K groups
+    typedef GemmCfg<2, 2, 1, 1, 3, 2, 2> T64x64k2;     // small tiles with two K groups for problems with few of the
+    typedef GemmCfg<2, 2, 2, 1, 3, 2, 2> T128x64k2;    // larger ones: 64 x 64 and 128 (N) x 64 (M)
     // Estimated time in microseconds, fitted to measurements on uniform random operands (the clock is
     // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
     // one-workgroup-per-CU shapes run ceil(tiles / 256) rounds of (fixed + per-K-tile) each.  With two
@@ -607,12 +613,19 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
         // ring does not help there; filling the idle CUs would take a split of K across workgroups.
         if (pick == 2 && tiles(256, 128) <= CUS) pick = 5;
         if (tiles(128, 128) <= CUS) pick = 4;
+        // Fewer tiles still: the smallest tile shape that still gives every CU at most one workgroup (measured at
+        // K = 4096, N = 4096: 256 tokens 11 us on 64 x 64 tiles against 17 on 128 x 128; 512 tokens 13 us on
+        // 128 x 64 against 18).
+        if (tiles(128, 64) <= CUS) pick = 7;
+        if (tiles(64, 64) <= CUS) pick = 6;
     }
     if (pick == 1) return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 2) return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 4) return launch_cfg<T128x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 5) return launch_cfg<T256x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 6) return launch_cfg<T64x64k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 7) return launch_cfg<T128x64k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 

@@ -110,7 +110,7 @@ def test_linear_matches_oracle(oracle, M, N, K, use_ref):
     assert np.array_equal(got["y"], ref["y"])          # same fp32 recipe on both sides: expected identical
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("M,N,K", [(128, 512, 512), (257, 513, 1024), (300, 260, 4096), (100, 300, 640), (33, 1000, 130),
                                    (520, 390, 896)])
 def test_every_prefill_tile_shape(oracle, M, N, K, tile):

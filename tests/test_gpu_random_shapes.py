@@ -35,7 +35,7 @@ def test_random_shapes_against_the_simple_kernel(seed):
         d = torch.from_numpy(rng.uniform(0.5, 2.0, M).astype(np.float32)).cuda() if rng.integers(0, 2) else None
         s_a = float(rng.uniform(0.01, 1.0))
         y_ref, a_ref = fptq.fptq_w4a4_linear_ref(xq, wq, M, N, K, s_a, s_w, d, want_acc=True)
-        tile = int(rng.integers(0, 7))
+        tile = int(rng.integers(0, 9))
         fptq.fptq_set_gemm_tile(tile)
         try:
             y, a = fptq.fptq_w4a4_linear(xq, wq, M, N, K, s_a, s_w, d, want_acc=True)

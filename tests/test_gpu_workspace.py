@@ -20,15 +20,15 @@ def zero_ws(M, N, K, extra=0):
 def test_workspace_size_rules():
     assert fptq.fptq_linear_workspace_bytes(2048, 11008, 4096) == 0          # enough tiles already
     assert fptq.fptq_linear_workspace_bytes(8, 4096, 4096) == 0              # few-token kernel
-    assert fptq.fptq_linear_workspace_bytes(256, 4096, 4096) == 0            # K too short to split
+    assert fptq.fptq_linear_workspace_bytes(256, 4096, 8192) == 0            # K too short to split
     n = fptq.fptq_linear_workspace_bytes(256, 4096, 14336)                   # 64 tiles, 4 ranges of 28 K tiles
     assert n == (64 + 4 * 64 * 64 * 256) * 4
     with pytest.raises(fptq.FptqError):
         fptq.fptq_linear_workspace_bytes(0, 4096, 4096)
 
 
-@pytest.mark.parametrize("M,N,K", [(129, 300, 8192), (200, 260, 8320), (257, 130, 12290), (300, 1000, 8192), (512, 128, 14336),
-                                   (130, 2100, 8192)])
+@pytest.mark.parametrize("M,N,K", [(129, 300, 12288), (200, 260, 12416), (257, 130, 12290), (300, 1000, 12288), (512, 128, 14336),
+                                   (130, 2100, 12288)])
 def test_split_matches_oracle(oracle, M, N, K):
     case = synth.LinearCase("ws", f"m{M}", M, N, K, "normal", 0.0, 3, 4.0, synth.MODE_RMS, M + N + K)
     inp = synth.draw(case)
@@ -45,7 +45,7 @@ def test_split_matches_oracle(oracle, M, N, K):
     assert int(counters.max()) == 0          # arrival counters are back to zero
 
 
-@pytest.mark.parametrize("M,N,K", [(256, 4096, 8192), (512, 4096, 14336), (1024, 1024, 8192), (129, 6144, 12288), (384, 2050, 8200),
+@pytest.mark.parametrize("M,N,K", [(256, 4096, 12288), (512, 4096, 14336), (1024, 1024, 16384), (129, 6144, 12288), (384, 2050, 12296),
                                    (300, 5000, 28672)])
 def test_split_equals_unsplit_at_size(M, N, K):
     torch.manual_seed(M + N + K)
@@ -88,7 +88,7 @@ def test_split_never_reads_a_previous_call_s_partials():
 
 
 def test_workspace_too_small_or_absent_falls_back():
-    M, N, K = 256, 1024, 8192
+    M, N, K = 256, 1024, 12288
     torch.manual_seed(1)
     xq = torch.randint(0, 256, (fptq.fptq_packed_bytes(M, K),), dtype=torch.uint8, device="cuda")
     wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(N, K),), dtype=torch.uint8, device="cuda")
