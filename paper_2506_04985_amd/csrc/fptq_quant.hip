@@ -11,7 +11,6 @@ namespace fptq {
 
 constexpr int QT = 256;        // threads per row
 constexpr int QCHUNK = 8;      // bf16 values per 16-byte load
-constexpr int QREG_CHUNKS = 16; // chunks a thread keeps in registers: rows up to 256*8*16 = 32768 values
 
 __device__ inline float bf16_to_f32(uint32_t bits) { return __uint_as_float(bits << 16); }
 
@@ -45,8 +44,14 @@ __device__ inline void store_word(uint8_t *out, int64_t M, int64_t t, int64_t k0
     *reinterpret_cast<uint32_t *>(out + ((k0 / KT) * M + t) * SEG + (k0 % KT) / 2) = word;
 }
 
-// VEC: K is a multiple of 8, so every row starts 16-byte aligned and chunks never straddle K.
-template <int MODE, bool VEC>
+typedef unsigned int q_v4u __attribute__((ext_vector_type(4)));
+constexpr int Q_RSRC_FLAGS = 0x00020000;     // raw buffer, bounds-checked: reads past num_records return zero
+
+// One workgroup per row.  CH > 0: K % 8 == 0, 16-byte aligned rows of at most 2048 * CH values, kept in
+// registers (CH 16-byte chunks per thread) between the reduction and the quantizer and read through a row-sized
+// buffer descriptor, so chunks past the end read as zero and nothing branches but the store of a chunk past
+// the padded width.  CH == 0: any K and alignment, two passes over the row.
+template <int MODE, int CH>
 __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K, float eps,
                                                           const float *__restrict__ row_in, float inv_s_a, int zoff,
                                                           uint8_t *__restrict__ out, float *__restrict__ row_out)
@@ -57,22 +62,19 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
     const int64_t Kpad = k_tiles(K) * KT;
     const int tid = threadIdx.x;
 
-    uint4 regs[QREG_CHUNKS];
-    const bool in_regs = VEC && K <= (int64_t)QT * QCHUNK * QREG_CHUNKS;
-    if (in_regs) {
+    q_v4u regs[CH > 0 ? CH : 1];
+    if (CH > 0) {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)row, 0, (int)K * 2, Q_RSRC_FLAGS);
 #pragma unroll
-        for (int i = 0; i < QREG_CHUNKS; ++i) {
-            int64_t k0 = ((int64_t)i * QT + tid) * QCHUNK;
-            regs[i] = k0 < K ? *reinterpret_cast<const uint4 *>(row + k0) : make_uint4(0, 0, 0, 0);
-        }
+        for (int i = 0; i < CH; ++i) regs[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (i * QT + tid) * 16, 0, 0);
     }
 
     float r = 1.0f;
     if (MODE == FPTQ_SCALE_RMS) {
         double ss = 0.0;
-        if (in_regs) {
+        if (CH > 0) {
 #pragma unroll
-            for (int i = 0; i < QREG_CHUNKS; ++i) {
+            for (int i = 0; i < CH; ++i) {
                 const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -96,15 +98,16 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
     const float c = (MODE == FPTQ_SCALE_NONE) ? inv_s_a : r * inv_s_a;
     if (tid == 0 && row_out) row_out[t] = r;
 
-    if (in_regs) {
+    if (CH > 0) {
+        // chunk i of thread h is values 8 (256 i + h) ..: K tile 16 i + h / 16, byte 4 (h % 16) of the row's segment
+        uint8_t *orow = out + (((int64_t)(tid >> 4) * M + t) * SEG + (tid & 15) * 4);
 #pragma unroll
-        for (int i = 0; i < QREG_CHUNKS; ++i) {
-            int64_t k0 = ((int64_t)i * QT + tid) * QCHUNK;
-            if (k0 < Kpad) {
-                const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-                const uint32_t word = quant_chunk(w, c, zoff);
-                store_word(out, M, t, k0, k0 < K ? word : 0u);
-            }
+        for (int i = 0; i < CH; ++i) {
+            const int k0 = (i * QT + tid) * QCHUNK;
+            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+            uint32_t word = quant_chunk(w, c, zoff);
+            if (k0 >= (int)K) word = 0u;                          // K padding stays zero
+            if (k0 < (int)Kpad) *reinterpret_cast<uint32_t *>(orow + (int64_t)(16 * i) * M * SEG) = word;
         }
     } else {
         for (int64_t k0 = (int64_t)tid * QCHUNK; k0 < Kpad; k0 += (int64_t)QT * QCHUNK) {
@@ -118,10 +121,6 @@ __global__ __launch_bounds__(QT) void quantize_act_kernel(const uint16_t *__rest
         }
     }
 }
-
-// One wave per row, CH 16-byte chunks per lane (K <= 512 * CH, K % 8 == 0, 16-byte aligned rows).
-typedef unsigned int q_v4u __attribute__((ext_vector_type(4)));
-constexpr int Q_RSRC_FLAGS = 0x00020000;     // raw buffer, bounds-checked: reads past num_records return zero
 
 // One wave per row, for rows of at most 512 * CH values (K % 8 == 0).  The row is read through a
 // row-sized buffer descriptor, so chunks past its end read as zero and neither the loads nor the
@@ -289,10 +288,19 @@ static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps
 #undef FPTQ_WAVE_CASE
         return hipGetLastError();
     }
-    if (vec)
-        quantize_act_kernel<MODE, true><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out);
-    else
-        quantize_act_kernel<MODE, false><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out);
+#define FPTQ_ROW_CASE(CH)                                                                                                   \
+    if (vec && Kpad <= 2048 * CH) {                                                                                         \
+        quantize_act_kernel<MODE, CH><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out);            \
+        return hipGetLastError();                                                                                           \
+    }
+    // chunks per thread: 7 and 14 are the Llama-3 FFN widths 14336 and 28672
+    FPTQ_ROW_CASE(7)
+    FPTQ_ROW_CASE(8)
+    FPTQ_ROW_CASE(12)
+    FPTQ_ROW_CASE(14)
+    FPTQ_ROW_CASE(16)
+#undef FPTQ_ROW_CASE
+    quantize_act_kernel<MODE, 0><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out);
     return hipGetLastError();
 }
 
