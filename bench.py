@@ -333,6 +333,17 @@ def activation_summary(torch, fptq, dev, x_gu, x_dn, r_dn, s_gu, s_dn, gate, dow
     b_b = M * down.K * 2.5 + 8 * M
     entry("quantize_rms_2048x4096", graph_time_us(torch, lambda: fptq.fptq_quantize_act(x_gu, s_gu, gate.mode, gate.eps, None, out=xq_a, row_scale_out=r_out)), b_a)
     entry("quantize_given_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act(x_dn, s_dn, down.mode, down.eps, r_dn, out=xq_b, row_scale_out=r_out)), b_b)
+    # the same two quantizers on inputs that are not in any cache: cycled over > 320 MB of copies of X.  (Behind its
+    # producer the input is usually still in the 256 MB last-level cache, which is what the figures above see.)
+    def cold(x, fn):
+        copies = [x.clone() for _ in range((320 << 20) // (x.numel() * 2) + 1)]
+        state = {"i": 0}
+        def call():
+            fn(copies[state["i"] % len(copies)])
+            state["i"] += 1
+        return graph_time_us(torch, call, iters=2 * len(copies), replays=3)
+    entry("quantize_rms_2048x4096_cold_input", cold(x_gu, lambda xx: fptq.fptq_quantize_act(xx, s_gu, gate.mode, gate.eps, None, out=xq_a, row_scale_out=r_out)), b_a)
+    entry("quantize_given_2048x11008_cold_input", cold(x_dn, lambda xx: fptq.fptq_quantize_act(xx, s_dn, down.mode, down.eps, r_dn, out=xq_b, row_scale_out=r_out)), b_b)
     entry("hadamard256_quantize_given_2048x11008", graph_time_us(torch, lambda: fptq.fptq_quantize_act_hadamard(x_dn, s_dn, 256, down.mode, down.eps, r_dn, out=xq_b, row_scale_out=r_out)), b_b)
     # the Llama-3-8B down-projection input (4096 tokens x 14336), whose largest power-of-two block is 2048
     x_l3 = torch.randn((4096, 14336), device=dev).to(torch.bfloat16)
