@@ -11,6 +11,7 @@ Passages followed:
   per-token residual scaling S_n          Sec. 3.1.3, Eq. (5)-(7)
   RMSNorm gain folded into the next linear  Sec. 4.1 (transforms and norm scales are merged)
   online Hadamard T_d before the down projection, block-wise for non-powers of 2   Sec. 3.1.4, App. D
+  residual rotation T_r and per-channel up/down scaler T_u (both fully mergeable)   Sec. 3.1.4, Sec. 3.2.1 (Eq. 8), App. H
   round-to-nearest weight quantization    Sec. 4 "RTN", App. D
 
 Readings where the text is inconsistent:
@@ -229,6 +230,36 @@ def merge_hadamard_down(Wd, block):
 
 def largest_pow2_divisor(K):
     return K & (-K)
+
+
+# ----------------------------------------------------------------------------- T_r and T_u
+def merge_residual_rotation(W_in, W_out, Tr):
+    """Rotating the residual stream, x' = x T_r (Sec. 3.1.4): every linear that reads the residual becomes
+    T_r^-1 W and every linear that writes to it W T_r, the placement the local objective of Sec. 3.2.1 sums
+    over.  An orthogonal T_r commutes with the gain-free RMS normalisation (row norms are kept), so nothing
+    runs at inference time.  W_in, W_out: lists of [d_in, d_out] matrices."""
+    Tr = np.asarray(Tr, np.float64)
+    Tr_inv = np.linalg.inv(Tr)
+    return [Tr_inv @ W for W in W_in], [W @ Tr for W in W_out]
+
+
+def merge_up_down_scaler(Wu, Wd, u):
+    """Per-channel scaler T_u = diag(u) between the up and the down projection (Sec. 3.1.4, App. H): the up
+    projection's output channels are scaled, W_u diag(u), and the down projection undoes it, diag(1/u) W_d.
+    The gate branch multiplies element-wise and is left alone, so (act(x W_g) * (x W_u diag(u))) diag(1/u) W_d
+    is the original MLP."""
+    u = np.asarray(u, np.float64)
+    return np.asarray(Wu, np.float64) * u[None, :], np.asarray(Wd, np.float64) / u[:, None]
+
+
+def random_orthogonal(rng, d):
+    Q, R = np.linalg.qr(rng.standard_normal((d, d)))
+    return Q * np.sign(np.diag(R))
+
+
+def gated_mlp(x, Wg, Wu, Wd):
+    g = x @ Wg
+    return ((g / (1.0 + np.exp(-g))) * (x @ Wu)) @ Wd
 
 
 # ----------------------------------------------------------------------------- weight quantizer

@@ -195,3 +195,45 @@ def test_static_scale_rules():
     assert 0 < s3 < s_inf                    # the L3 grid clips the outlier
     err = lambda s: np.sum(np.abs(x - s * np.clip(np.rint(x / s), -8, 7)) ** 3)
     assert err(float(s3)) <= err(float(s_inf))
+
+
+def test_residual_rotation_is_mergeable_and_commutes_with_the_norm():
+    """x' = x T_r with every reader T_r^-1 W and every writer W T_r (Sec. 3.1.4): a two-block pre-norm residual
+    network gives the rotated output, block by block, and a non-orthogonal T_r does not (the norm sees it)."""
+    rng = np.random.default_rng(21)
+    d, f, L = 24, 40, 6
+    X = rng.standard_normal((L, d)) * np.exp(rng.standard_normal((L, 1)))
+    Wg, Wu, Wd = (rng.standard_normal((d, f)) / 5, rng.standard_normal((d, f)) / 5, rng.standard_normal((f, d)) / 5)
+    W1, W2 = rng.standard_normal((d, d)) / 4, rng.standard_normal((d, d)) / 4      # a second, purely linear block: in, out
+
+    def net(X, W1, W2, Wg, Wu, Wd):
+        Z = X + (X / T.rms(X)) @ W1 @ W2
+        return Z + T.gated_mlp(Z / T.rms(Z), Wg, Wu, Wd)
+
+    want = net(X, W1, W2, Wg, Wu, Wd)
+    Tr = T.random_orthogonal(rng, d)
+    (W1r, Wgr, Wur), (W2r, Wdr) = T.merge_residual_rotation([W1, Wg, Wu], [W2, Wd], Tr)
+    got = net(X @ Tr, W1r, W2r, Wgr, Wur, Wdr)
+    assert np.abs(got - want @ Tr).max() <= 1e-10 * np.abs(want).max()
+    bad = Tr * (1.0 + 0.3 * np.arange(d))[None, :]                                 # invertible, not orthogonal
+    (W1b, Wgb, Wub), (W2b, Wdb) = T.merge_residual_rotation([W1, Wg, Wu], [W2, Wd], bad)
+    assert np.abs(net(X @ bad, W1b, W2b, Wgb, Wub, Wdb) - want @ bad).max() > 1e-3 * np.abs(want).max()
+
+
+def test_up_down_scaler_is_function_preserving_also_with_the_hadamard():
+    """T_u merged into W_u and W_d (Sec. 3.1.4, App. H) leaves the gated MLP unchanged, alone and stacked with the
+    block-wise Hadamard in front of the down projection; scaling the gate branch instead would not."""
+    rng = np.random.default_rng(22)
+    d, f, L = 16, 96, 5                                      # f = 3 * 32: a Hadamard block of 32
+    x = rng.standard_normal((L, d))
+    Wg, Wu, Wd = rng.standard_normal((d, f)) / 4, rng.standard_normal((d, f)) / 4, rng.standard_normal((f, d)) / 6
+    u = np.exp(rng.standard_normal(f))
+    want = T.gated_mlp(x, Wg, Wu, Wd)
+    Wu2, Wd2 = T.merge_up_down_scaler(Wu, Wd, u)
+    assert np.abs(T.gated_mlp(x, Wg, Wu2, Wd2) - want).max() <= 1e-12 * np.abs(want).max()
+    g = x @ Wg
+    h = (g / (1.0 + np.exp(-g))) * (x @ Wu2)                 # what the online transform sees
+    Td = T.block_hadamard_matrix(f, 32)
+    assert np.abs((h @ Td) @ T.merge_hadamard_down(Wd2, 32) - want).max() <= 1e-12 * np.abs(want).max()
+    Wg_bad = Wg * u[None, :]                                 # the gate goes through a nonlinearity: not mergeable there
+    assert np.abs(T.gated_mlp(x, Wg_bad, Wu, Wd2) - want).max() > 1e-3 * np.abs(want).max()
