@@ -281,19 +281,25 @@ def attainable_summary(torch, fptq, dev):
 
 
 def few_tile_summary(torch, fptq, dev):
-    """Llama-3-8B down projection (N = 4096, K = 14336) at 256 tokens: 64 output tiles for 256 CUs.  fptq_w4a4_linear
-    against fptq_w4a4_linear_ws, which splits K over four workgroups per tile through a caller workspace."""
-    M, N, K = 256, 4096, 14336
-    xq = torch.randint(0, 256, (fptq.fptq_packed_bytes(M, K),), dtype=torch.uint8, device=dev)
-    wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(N, K),), dtype=torch.uint8, device=dev)
-    s_w = torch.rand(N, device=dev) * 0.015 + 0.005
-    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-    ws = torch.zeros(fptq.fptq_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=dev)
-    plain = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.5, s_w, out=y), iters=10, replays=3)
-    split = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, 0.5, s_w, ws, out=y), iters=10, replays=3)
-    ops = 2 * M * N * K
-    return {"shape": "M 256 x N 4096 x K 14336", "plain_us": round(plain, 1), "plain_TOPS": round(ops / plain / 1e6, 1),
-            "workspace_us": round(split, 1), "workspace_TOPS": round(ops / split / 1e6, 1), "workspace_MiB": ws.numel() >> 20}
+    """256 tokens, where the large tiles would leave most CUs idle: the Llama-3-8B down projection (N = 4096,
+    K = 14336; a 64 x 64 tile per CU) and the Llama-3-70B key projection (N = 1024, K = 8192; 64 such tiles), the
+    latter also through fptq_w4a4_linear_ws, which splits K over four workgroups per tile through a caller workspace."""
+    res = []
+    for M, N, K in ((256, 4096, 14336), (256, 1024, 8192)):
+        xq = torch.randint(0, 256, (fptq.fptq_packed_bytes(M, K),), dtype=torch.uint8, device=dev)
+        wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(N, K),), dtype=torch.uint8, device=dev)
+        s_w = torch.rand(N, device=dev) * 0.015 + 0.005
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ops = 2 * M * N * K
+        plain = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.5, s_w, out=y), iters=10, replays=3)
+        row = {"shape": f"M {M} x N {N} x K {K}", "plain_us": round(plain, 1), "plain_TOPS": round(ops / plain / 1e6, 1)}
+        nbytes = fptq.fptq_linear_workspace_bytes(M, N, K)
+        if nbytes:
+            ws = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+            split = graph_time_us(torch, lambda: fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, 0.5, s_w, ws, out=y), iters=10, replays=3)
+            row.update({"workspace_us": round(split, 1), "workspace_TOPS": round(ops / split / 1e6, 1), "workspace_MiB": round(nbytes / 2**20, 1)})
+        res.append(row)
+    return res
 
 
 def graph_time_us(torch, fn, iters=20, replays=5):

@@ -168,9 +168,9 @@ int fptq_w4a4_linear_zp(const void *xq_packed, const void *w_packed, int64_t M, 
                         void *y_bf16, int32_t *acc_dbg, void *stream);
 
 /*
- * fptq_w4a4_linear with a workspace.  Between about 129 and 1024 tokens a matrix with few output channels
- * gives the prefill kernel fewer output tiles than the device has CUs; with a workspace the kernel splits K
- * over several workgroups per tile, which leave their partial INT32 accumulators in the workspace, and the
+ * fptq_w4a4_linear with a workspace.  A problem with at most 128 output tiles of 64 x 64 (M * N up to about
+ * half a million outputs) and K >= 6144 leaves half of the CUs or more idle; with a workspace the kernel splits
+ * K over up to four workgroups per tile, which leave their partial INT32 accumulators in the workspace, and the
  * last one to arrive adds them (integers: the result does not depend on the order) and writes y.
  *   workspace        device, 256-byte aligned, at least fptq_linear_workspace_bytes(M, N, K) bytes, or NULL.
  *                    It must be zero-filled once before its first use; every call leaves the part that has
@@ -193,7 +193,7 @@ int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M,
 /* Testing / tuning knob for the prefill kernel's tile shape (process-wide, not thread-safe against
  * concurrent fptq_w4a4_linear calls): 0 = chosen per problem (default), 1 = 256x256, 2 = 192 (N) x
  * 256 (M), 3 = 256 (N) x 128 (M), 4 = 256 x 128 with two workgroups per CU, 5 = 128 x 128 and
- * 6 = 256 x 128 with two K groups per workgroup, 7 = 64 x 64 and 8 = 128 (N) x 64 (M) with two K groups.
+ * 6 = 256 x 128 with two K groups per workgroup, 7 = 64 x 64 and 8 = 128 (N) x 64 (M) with four K groups.
  * A forced shape also sends calls with few tokens to the prefill kernel.  Results do not depend on it. */
 int fptq_set_gemm_tile(int tile);
 

@@ -36,7 +36,7 @@ constexpr int MAX_SPLITS = 4;     // K ranges per output tile in the split-K var
 
 // OCC_ = workgroups meant to share a CU (caps the register budget: 512 / OCC_ per lane).  KS_ = K groups:
 // KS_ sets of WAVES waves work on the same output tile, set g on K tiles g, g + KS_, ..., each with its own
-// LDS ring; their accumulators are added through LDS before the epilogue.  A problem with at most one
+// LDS ring; their accumulators are added through LDS and every group runs its share of the epilogue.  A problem with at most one
 // workgroup per CU runs one wave per SIMD, which cannot hide its own LDS and VALU latencies; a second K group
 // gives every SIMD a second wave without needing more output tiles.
 // SPLIT_: several workgroups share an output tile, each on a contiguous range of K tiles; they leave their
@@ -59,7 +59,13 @@ struct GemmCfg {
     static constexpr int HALF_LOADS = (W_LOADS < 2 ? W_LOADS : 2) + (X_LOADS < 2 ? X_LOADS : 2);
     static_assert(STAGES >= 3, "pipeline needs three stages");
     static_assert(TN <= 4, "a wave's channel run must fit 16 lanes of 8 channels in the epilogue");
-    static_assert(KS == 1 || TN * TM * 16 * WAVES * 64 * 4 <= LDS_BYTES, "the K groups' accumulators are added through LDS");
+    // After the K loop the K groups exchange accumulators so that each ends up with the sum of SUBS of the wave's
+    // TN x TM sub-tiles (counted along n first): TNE along n, TME along m.
+    static constexpr int SUBS = TN * TM / KS;
+    static constexpr int TNE = SUBS >= TN ? TN : SUBS, TME = SUBS >= TN ? SUBS / TN : 1;
+    static constexpr int NSC = (TNE * 32 + 63) / 64;           // channel scales a lane fetches for the epilogue
+    static_assert(TN * TM % KS == 0 && TNE * TME == SUBS && TN % TNE == 0, "the K groups share the sub-tiles evenly, in runs along n");
+    static_assert((KS - 1) * TN * TM * WAVES * 4096 <= LDS_BYTES, "the K groups' accumulators are added through LDS");
 };
 
 // widen two packed dwords (16 nibbles) into one MFMA operand of 16 bytes, each 16 * value
@@ -90,6 +96,173 @@ template <int J>
 __device__ inline void load_chunk(__amdgpu_buffer_rsrc_t r, uint8_t *lds_base, int voff)
 {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, LDS_PTR(lds_base), 16, voff, 0, J * 1024, 0);
+}
+
+// Channel scales (and, with a zero point, the weight row sums) of a run of TNE * 32 channels, one or two per lane.
+template <int TNE>
+__device__ inline void load_scales(float (&scv)[(TNE * 32 + 63) / 64], int32_t (&zwv)[(TNE * 32 + 63) / 64],
+                                   const float *__restrict__ s_w, const int32_t *__restrict__ wsum, int nw0, int N, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < (TNE * 32 + 63) / 64; ++i) {
+        const int n = min(nw0 + min(lane + 64 * i, TNE * 32 - 1), N - 1);
+        scv[i] = s_w[n];
+        zwv[i] = wsum ? wsum[n] : 0;
+    }
+}
+
+// What a wave does with its finished sub-tiles a[t][i] (t < TNE along n from channel nw0, i < TME along m from
+// token mw0; sub-tile numbers sub0 .. of the wave's TN x TM, counted along n first): the split-K exchange, then
+// the epilogue.
+template <class C, int TNE, int TME, bool ALIGNED, bool DUMP>
+__device__ inline void finish(v16i (&a)[TNE][TME], const float (&scv)[(TNE * 32 + 63) / 64],
+                              const int32_t (&zwv)[(TNE * 32 + 63) / 64], uint8_t *lds, int wave_all, int wave, int lane,
+                              int sub0, int nw0, int mw0, int M, int N, float s_a, const float *__restrict__ d, int zp,
+                              const int32_t *__restrict__ wsum, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out,
+                              int32_t *ws, int splits, int split, int pid, int total)
+{
+    const int fi = lane & 31, fg = lane >> 5;
+    // ---- split K: leave the partial tile in the workspace, count the arrival, and let the last workgroup of
+    // the tile add the others' partials and go on to the epilogue.  Nobody waits for anybody, so there is nothing
+    // to hang on.  The workgroups of a tile run on different XCDs, whose L2s are not coherent with each other, and
+    // a device-wide fence would write back and invalidate a whole L2 per workgroup; instead the partials are
+    // stored and loaded with the device-coherent cache policy (sc0 sc1: written through to, and read from, the
+    // memory side), the stores are complete (vmcnt) before the arrival is counted, and the count is an atomic
+    // at the same scope.  Workspace: [total] arrival counters (zero between calls), then
+    // [splits][total][sub-tile][quad][threads of a K group] partials as 16-byte quads, lane-contiguous.
+    if (C::SPLIT) {
+        constexpr int TPG = C::WAVES * 64, COHERENT = 1 | 16;     // aux bits: sc0, sc1
+        const int64_t slice = (int64_t)C::ACC_REGS * TPG;
+        int32_t *counters = ws, *parts = ws + ((total + 63) & ~63);
+        int *flag = reinterpret_cast<int *>(lds + C::LDS_BYTES - 16);     // clear of the epilogue's patches
+        const int qoff = (wave * 64 + lane) * 16 + sub0 * (4 * TPG * 16);
+        const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(parts + ((int64_t)split * total + pid) * slice), 0, (int)slice * 4, RSRC_FLAGS);
+#pragma unroll
+        for (int i = 0; i < TME; ++i)
+#pragma unroll
+            for (int t = 0; t < TNE; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const v4i v = {a[t][i][4 * q], a[t][i][4 * q + 1], a[t][i][4 * q + 2], a[t][i][4 * q + 3]};
+                    __builtin_amdgcn_raw_buffer_store_b128(v, mine, qoff + ((i * TNE + t) * 4 + q) * (TPG * 16), 0, COHERENT);
+                }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // this wave's partials have reached the memory side
+        __syncthreads();
+        if (threadIdx.x == 0) *flag = __hip_atomic_fetch_add(counters + pid, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*flag != splits - 1) return;             // the whole workgroup: not the last one of this tile
+        // the other (at most MAX_SPLITS - 1) partial tiles, read side by side so that their latencies overlap
+        __amdgpu_buffer_rsrc_t other[MAX_SPLITS - 1];
+#pragma unroll
+        for (int j = 0; j < MAX_SPLITS - 1; ++j) {
+            const int s2 = (split + 1 + j) % splits;            // j < splits - 1: every other split once
+            other[j] = __builtin_amdgcn_make_buffer_rsrc((void *)(parts + ((int64_t)s2 * total + pid) * slice), 0,
+                                                         j < splits - 1 ? (int)slice * 4 : 0, RSRC_FLAGS);
+        }
+#pragma unroll
+        for (int i = 0; i < TME; ++i)
+#pragma unroll
+            for (int t = 0; t < TNE; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v4i v[MAX_SPLITS - 1];
+#pragma unroll
+                    for (int j = 0; j < MAX_SPLITS - 1; ++j)      // an empty descriptor (j >= splits - 1) reads zeros
+                        v[j] = __builtin_amdgcn_raw_buffer_load_b128(other[j], qoff + ((i * TNE + t) * 4 + q) * (TPG * 16), 0, COHERENT);
+#pragma unroll
+                    for (int j = 0; j < MAX_SPLITS - 1; ++j)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) a[t][i][4 * q + e] += v[j][e];
+                }
+        if (threadIdx.x == 0) counters[pid] = 0;     // as it was found, for the next call
+    }
+
+    // ---- epilogue.  W was the A operand, so an accumulator tile is [n][m]: a lane owns token
+    // m = lane % 32 and, per register quad q, four consecutive output channels
+    // n = 8 q + 4 (lane / 32) + (r % 4).  The register holds 256 * acc; (float)(256 * acc) equals
+    // 256 * (float)acc exactly (acc has fewer than 24 significant bits), and the 2^-8 is folded into
+    // the channel scale, which is exact as well, so y = bf16((float)acc * (s_a * s_w[n]) [* d_t]) to
+    // the bit.  The bf16 results go through a wave-private LDS patch ([32 tokens][TNE * 32 channels],
+    // padded rows) so that HBM sees whole 16-byte-per-lane row segments instead of scattered quads.
+    constexpr int WN = TNE * 32;                      // channels of this wave's run
+    constexpr int PATCH_STRIDE = WN * 2 + 16;         // bytes per token row in the patch
+    // With an activation zero point z the sum wanted is sum_k (v - z) w = acc - z * wsum[n]; the
+    // correction is staged as 256 * z * wsum[n] next to the scales (|.| < 2^31 for K <= 65535).
+    constexpr int WAVE_LDS = 32 * PATCH_STRIDE + WN * 8;
+    uint8_t *patch = lds + wave_all * WAVE_LDS;
+    float *cwbuf = reinterpret_cast<float *>(patch + 32 * PATCH_STRIDE);
+    int32_t *zwbuf = reinterpret_cast<int32_t *>(cwbuf + WN);
+#pragma unroll
+    for (int i = 0; i < (WN + 63) / 64; ++i) {
+        const int c = lane + 64 * i;
+        if (c < WN) {
+            cwbuf[c] = (s_a * scv[i]) * 0.00390625f;
+            if (wsum) zwbuf[c] = (zp * zwv[i]) * 256;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int tm = 0; tm < TME; ++tm) {
+        const int mt0 = mw0 + tm * 32;
+        const int m = mt0 + fi;
+        const float dm = (d && m < M) ? d[m] : 1.0f;
+#pragma unroll
+        for (int tn = 0; tn < TNE; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 c4 = *reinterpret_cast<const float4 *>(cwbuf + tn * 32 + 8 * q + 4 * fg);
+                int32_t a4[4] = {a[tn][tm][4 * q + 0], a[tn][tm][4 * q + 1], a[tn][tm][4 * q + 2], a[tn][tm][4 * q + 3]};
+                if (wsum) {
+                    const int4 z4 = *reinterpret_cast<const int4 *>(zwbuf + tn * 32 + 8 * q + 4 * fg);
+                    a4[0] -= z4.x, a4[1] -= z4.y, a4[2] -= z4.z, a4[3] -= z4.w;
+                }
+                float yf[4] = {(float)a4[0] * c4.x, (float)a4[1] * c4.y, (float)a4[2] * c4.z, (float)a4[3] * c4.w};
+                if (d) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) yf[e] = yf[e] * dm;
+                }
+                *reinterpret_cast<uint2 *>(patch + fi * PATCH_STRIDE + (tn * 32 + 8 * q + 4 * fg) * 2) =
+                    make_uint2(pack_bf16(yf[0], yf[1]), pack_bf16(yf[2], yf[3]));
+            }
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+        __builtin_amdgcn_wave_barrier();
+        // read back row segments: 16 bytes (8 channels) per lane, WN / 8 lanes per token row
+        // (lanes per row rounded up to a power of two; the surplus lanes idle)
+        constexpr int LANES_PER_ROW = WN / 8 <= 4 ? 4 : WN / 8 <= 8 ? 8 : 16, ROWS_PER_PASS = 64 / LANES_PER_ROW;
+#pragma unroll
+        for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
+            const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW, col = (lane % LANES_PER_ROW) * 8;
+            const bool live = col < WN;
+            const uint4 v = live ? *reinterpret_cast<const uint4 *>(patch + row * PATCH_STRIDE + col * 2) : make_uint4(0, 0, 0, 0);
+            const int mm = mt0 + row, nn = nw0 + col;
+            if (live && mm < M && nn < N) {
+                uint16_t *dst = y + (int64_t)mm * N + nn;
+                if (ALIGNED) {       // N % 8 == 0: the segment is whole and 16-byte aligned
+                    *reinterpret_cast<uint4 *>(dst) = v;
+                } else {
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (nn + e < N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+        __builtin_amdgcn_wave_barrier();
+        if (DUMP) {      // parity dump of the integer accumulators (never a timed path)
+#pragma unroll
+            for (int tn = 0; tn < TNE; ++tn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int n = nw0 + tn * 32 + 8 * q + 4 * fg + e;
+                        if (m < M && n < N) acc_out[(int64_t)m * N + n] = a[tn][tm][4 * q + e] >> 8;
+                    }
+        }
+    }
 }
 
 template <class C, bool ALIGNED, bool DUMP>
@@ -311,182 +484,65 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
     __builtin_amdgcn_s_barrier();
 
-    // ---- K groups: groups 1.. hand their accumulators to group 0 through LDS (integers: exact, order-free),
-    // one group at a time, register-major so that every access is a run of consecutive words; then they leave
-    // (nothing below synchronises across waves).
+    // ---- K groups: the accumulators of the KS groups are added through LDS (integers: exact, order-free) and the
+    // sum stays distributed: group g ends up with sub-tiles g * P .. g * P + P - 1 of the wave's TN x TM (counted
+    // along n first), so every wave of the workgroup adds 1 / KS of the registers and runs 1 / KS of the epilogue.
+    // Every wave first stores the sub-tiles that belong to other groups (16-byte quads, lane-contiguous), then,
+    // after one barrier, adds what the others stored for it.
     if (C::KS > 1) {
-        int32_t *red = reinterpret_cast<int32_t *>(lds) + wave * 64 + lane;
-        constexpr int RSTRIDE = C::WAVES * 64;
-#pragma unroll 1
-        for (int g = 1; g < C::KS; ++g) {
-            if (kg == g) {
+        constexpr int P = C::SUBS, TPG = C::WAVES * 64, QUAD_BYTES = TPG * 16;
+        const int tn0 = (kg * P) % C::TN, tm0 = (kg * P) / C::TN;
+        const int nw0 = n0 + (wave_n * C::TN + tn0) * 32;
+        float scv[C::NSC];
+        int32_t zwv[C::NSC];
+        load_scales<C::TNE>(scv, zwv, s_w, wsum, nw0, N, lane);      // in flight during the exchange
+        uint8_t *const xlane = lds + (wave * 64 + lane) * 16;
 #pragma unroll
-                for (int tn = 0; tn < C::TN; ++tn)
+        for (int f = 0; f < C::TN * C::TM; ++f) {
+            constexpr int KS1 = C::KS - 1;
+            const int h = f / P, p = f % P;                          // receiving group, position in its share
+            if (kg != h) {
+                const int sender = kg - (kg > h ? 1 : 0);
+                uint8_t *dst = xlane + ((h * KS1 + sender) * P + p) * (4 * QUAD_BYTES);
 #pragma unroll
-                    for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) red[((tn * C::TM + tm) * 16 + r) * RSTRIDE] = acc[tn][tm][r];
-            }
-            __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
-            __builtin_amdgcn_s_barrier();
-            if (kg == 0) {
-#pragma unroll
-                for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-                    for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) acc[tn][tm][r] += red[((tn * C::TM + tm) * 16 + r) * RSTRIDE];
-            }
-            __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
-            __builtin_amdgcn_s_barrier();
-        }
-        if (!C::SPLIT && kg != 0) return;
-    }
-
-    // ---- split K: leave the partial tile in the workspace, count the arrival, and let the last workgroup of
-    // the tile add the others' partials and go on to the epilogue.  Nobody waits for anybody, so there is nothing
-    // to hang on.  The workgroups of a tile run on different XCDs, whose L2s are not coherent with each other, and
-    // a device-wide fence would write back and invalidate a whole L2 per workgroup; instead the partials are
-    // stored and loaded with the device-coherent cache policy (sc0 sc1: written through to, and read from, the
-    // memory side), the stores are complete (vmcnt) before the arrival is counted, and the count is an atomic
-    // at the same scope.  Workspace: [total] arrival counters (zero between calls), then
-    // [splits][total][ACC_REGS / 4][threads of a K group] partials as 16-byte quads, lane-contiguous.
-    if (C::SPLIT) {
-        constexpr int TPG = C::WAVES * 64, QUADS = C::ACC_REGS / 4, COHERENT = 1 | 16;     // aux bits: sc0, sc1
-        const int64_t slice = (int64_t)C::ACC_REGS * TPG;
-        int32_t *counters = ws, *parts = ws + ((total + 63) & ~63);
-        int *flag = reinterpret_cast<int *>(lds + C::LDS_BYTES - 16);     // clear of the reduction and epilogue regions
-        const int qoff = (wave * 64 + lane) * 16;
-        if (kg == 0) {
-            const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(parts + ((int64_t)split * total + pid) * slice), 0, (int)slice * 4, RSRC_FLAGS);
-#pragma unroll
-            for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const v4i v = {acc[tn][tm][4 * q], acc[tn][tm][4 * q + 1], acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]};
-                        __builtin_amdgcn_raw_buffer_store_b128(v, mine, qoff + ((tn * C::TM + tm) * 4 + q) * (TPG * 16), 0, COHERENT);
-                    }
-            static_assert(QUADS == C::TN * C::TM * 4, "quads per lane");
-        }
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // this wave's partials have reached the memory side
-        __syncthreads();
-        if (tid == 0) *flag = __hip_atomic_fetch_add(counters + pid, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (*flag != splits - 1) return;             // the whole workgroup: not the last one of this tile
-        if (kg == 0) {
-            // the other (at most MAX_SPLITS - 1) partial tiles, read side by side so that their latencies overlap
-            __amdgpu_buffer_rsrc_t other[MAX_SPLITS - 1];
-#pragma unroll
-            for (int j = 0; j < MAX_SPLITS - 1; ++j) {
-                const int s2 = (split + 1 + j) % splits;            // j < splits - 1: every other split once
-                other[j] = __builtin_amdgcn_make_buffer_rsrc((void *)(parts + ((int64_t)s2 * total + pid) * slice), 0,
-                                                             j < splits - 1 ? (int)slice * 4 : 0, RSRC_FLAGS);
-            }
-#pragma unroll
-            for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        v4i v[MAX_SPLITS - 1];
-#pragma unroll
-                        for (int j = 0; j < MAX_SPLITS - 1; ++j)      // an empty descriptor (j >= splits - 1) reads zeros
-                            v[j] = __builtin_amdgcn_raw_buffer_load_b128(other[j], qoff + ((tn * C::TM + tm) * 4 + q) * (TPG * 16), 0, COHERENT);
-#pragma unroll
-                        for (int j = 0; j < MAX_SPLITS - 1; ++j)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[tn][tm][4 * q + e] += v[j][e];
-                    }
-        }
-        if (tid == 0) counters[pid] = 0;             // as it was found, for the next call
-        if (kg != 0) return;
-    }
-
-    // ---- epilogue.  W was the A operand, so an accumulator tile is [n][m]: a lane owns token
-    // m = lane % 32 and, per register quad q, four consecutive output channels
-    // n = 8 q + 4 (lane / 32) + (r % 4).  The register holds 256 * acc; (float)(256 * acc) equals
-    // 256 * (float)acc exactly (acc has fewer than 24 significant bits), and the 2^-8 is folded into
-    // the channel scale, which is exact as well, so y = bf16((float)acc * (s_a * s_w[n]) [* d_t]) to
-    // the bit.  The bf16 results go through a wave-private LDS patch ([32 tokens][TN * 32 channels],
-    // padded rows) so that HBM sees whole 16-byte-per-lane row segments instead of scattered quads.
-    constexpr int WN = C::TN * 32;                    // channels per wave
-    constexpr int PATCH_STRIDE = WN * 2 + 16;         // bytes per token row in the patch
-    // With an activation zero point z the sum wanted is sum_k (v - z) w = acc - z * wsum[n]; the
-    // correction is staged as 256 * z * wsum[n] next to the scales (|.| < 2^31 for K <= 65535).
-    constexpr int WAVE_LDS = 32 * PATCH_STRIDE + WN * 8;
-    uint8_t *patch = lds + wave * WAVE_LDS;
-    float *cwbuf = reinterpret_cast<float *>(patch + 32 * PATCH_STRIDE);
-    int32_t *zwbuf = reinterpret_cast<int32_t *>(cwbuf + WN);
-    const int nw0 = n0 + wave_n * WN;
-#pragma unroll
-    for (int c = lane; c < WN; c += 64) {
-        cwbuf[c] = (s_a * s_w[min(nw0 + c, N - 1)]) * 0.00390625f;
-        if (wsum) zwbuf[c] = (zp * wsum[min(nw0 + c, N - 1)]) * 256;
-    }
-    __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm) {
-        const int mw0 = m0 + (wave_m * C::TM + tm) * 32;
-        const int m = mw0 + fi;
-        const float dm = (d && m < M) ? d[m] : 1.0f;
-#pragma unroll
-        for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 c4 = *reinterpret_cast<const float4 *>(cwbuf + tn * 32 + 8 * q + 4 * fg);
-                int32_t a4[4] = {acc[tn][tm][4 * q + 0], acc[tn][tm][4 * q + 1], acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]};
-                if (wsum) {
-                    const int4 z4 = *reinterpret_cast<const int4 *>(zwbuf + tn * 32 + 8 * q + 4 * fg);
-                    a4[0] -= z4.x, a4[1] -= z4.y, a4[2] -= z4.z, a4[3] -= z4.w;
-                }
-                float yf[4] = {(float)a4[0] * c4.x, (float)a4[1] * c4.y, (float)a4[2] * c4.z, (float)a4[3] * c4.w};
-                if (d) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) yf[e] = yf[e] * dm;
-                }
-                *reinterpret_cast<uint2 *>(patch + fi * PATCH_STRIDE + (tn * 32 + 8 * q + 4 * fg) * 2) =
-                    make_uint2(pack_bf16(yf[0], yf[1]), pack_bf16(yf[2], yf[3]));
-            }
-        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
-        __builtin_amdgcn_wave_barrier();
-        // read back row segments: 16 bytes (8 channels) per lane, WN / 8 lanes per token row
-        // (lanes per row rounded up to a power of two; the surplus lanes idle)
-        constexpr int LANES_PER_ROW = WN / 8 <= 4 ? 4 : WN / 8 <= 8 ? 8 : 16, ROWS_PER_PASS = 64 / LANES_PER_ROW;
-#pragma unroll
-        for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
-            const int row = pass * ROWS_PER_PASS + lane / LANES_PER_ROW, col = (lane % LANES_PER_ROW) * 8;
-            const bool live = col < WN;
-            const uint4 v = live ? *reinterpret_cast<const uint4 *>(patch + row * PATCH_STRIDE + col * 2) : make_uint4(0, 0, 0, 0);
-            const int mm = mw0 + row, nn = nw0 + col;
-            if (live && mm < M && nn < N) {
-                uint16_t *dst = y + (int64_t)mm * N + nn;
-                if (ALIGNED) {       // N % 8 == 0: the segment is whole and 16-byte aligned
-                    *reinterpret_cast<uint4 *>(dst) = v;
-                } else {
-                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (nn + e < N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                for (int q = 0; q < 4; ++q) {
+                    const v16i &a = acc[f % C::TN][f / C::TN];
+                    *reinterpret_cast<v4i *>(dst + q * QUAD_BYTES) = v4i{a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
                 }
             }
         }
         __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
-        __builtin_amdgcn_wave_barrier();
-        if (DUMP) {      // parity dump of the integer accumulators (never a timed path)
+        __builtin_amdgcn_s_barrier();
+        v16i mine[C::TNE][C::TME];
 #pragma unroll
-            for (int tn = 0; tn < C::TN; ++tn)
+        for (int h = 0; h < C::KS; ++h) {
+            if (kg == h) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int p = 0; p < P; ++p) mine[p % C::TNE][p / C::TNE] = acc[(h * P + p) % C::TN][(h * P + p) / C::TN];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        int n = nw0 + tn * 32 + 8 * q + 4 * fg + e;
-                        if (m < M && n < N) acc_out[(int64_t)m * N + n] = acc[tn][tm][4 * q + e] >> 8;
-                    }
+                for (int sender = 0; sender < C::KS - 1; ++sender)
+#pragma unroll
+                    for (int p = 0; p < P; ++p)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const v4i v = *reinterpret_cast<const v4i *>(xlane + (((h * (C::KS - 1) + sender) * P + p) * 4 + q) * QUAD_BYTES);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) mine[p % C::TNE][p / C::TNE][4 * q + e] += v[e];
+                        }
+            }
         }
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+        __builtin_amdgcn_s_barrier();                                // the exchange area is free for the epilogue
+        finish<C, C::TNE, C::TME, ALIGNED, DUMP>(mine, scv, zwv, lds, wave_all, wave, lane, kg * P, nw0,
+                                                 m0 + (wave_m * C::TM + tm0) * 32, M, N, s_a, d, zp, wsum, y, acc_out, ws,
+                                                 splits, split, pid, total);
+    } else {
+        const int nw0 = n0 + wave_n * (C::TN * 32);
+        float scv[C::NSC];
+        int32_t zwv[C::NSC];
+        load_scales<C::TN>(scv, zwv, s_w, wsum, nw0, N, lane);
+        finish<C, C::TN, C::TM, ALIGNED, DUMP>(acc, scv, zwv, lds, wave_all, wave, lane, 0, nw0, m0 + wave_m * (C::TM * 32),
+                                               M, N, s_a, d, zp, wsum, y, acc_out, ws, splits, split, pid, total);
     }
 }
 
@@ -526,17 +582,18 @@ static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, in
                    : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits);
 }
 
-// ---- split K over workgroups, for problems whose 128 x 128 tiles cover less than half of the CUs.
-typedef GemmCfg<2, 2, 2, 2, 3, 1, 2, true> T128x128k2split;
+// ---- split K over workgroups, for problems whose 64 x 64 tiles cover at most half of the CUs.
+typedef GemmCfg<1, 1, 2, 2, 4, 1, 4, true> T64x64k4split;
 
 // Number of K ranges: as many as keep the workgroup count within the CUs, at most MAX_SPLITS, at least 16 K tiles
-// each, none empty.  The exchange of partials costs about as much as 16 K tiles of work and the unsplit kernel has
-// small tiles for such problems, so only long K is split (measured on N = 4096, M = 256: K = 14336 takes 31 us
-// unsplit and 25 split, K = 8192 18 and 19.5).
+// (four per K group) each, none empty.  The exchange of partials pays from K = 6144 on (measured on N = 1024,
+// M = 256: K = 4096 takes 8.0 us unsplit and 8.6 split, K = 6144 9.8 and 9.0, K = 14336 16.6 and 11.4, K = 28672
+// 28.3 and 16.7).
+static int64_t split_tiles(int64_t M, int64_t N) { return ((N + T64x64k4split::BN - 1) / T64x64k4split::BN) * ((M + T64x64k4split::BM - 1) / T64x64k4split::BM); }
 static int split_count(int64_t M, int64_t N, int64_t K)
 {
-    const int64_t tiles = ((N + 127) / 128) * ((M + 127) / 128), kt = k_tiles(K);
-    if (tiles > 128 || K > 131071 || kt < 96) return 1;
+    const int64_t tiles = split_tiles(M, N), kt = k_tiles(K);
+    if (tiles > 128 || K > 131071 || kt < 48) return 1;
     int64_t sp = 256 / tiles;
     if (sp > kt / 16) sp = kt / 16;
     if (sp > MAX_SPLITS) sp = MAX_SPLITS;
@@ -549,8 +606,8 @@ int64_t linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     const int sp = split_count(M, N, K);
     if (sp < 2) return 0;
-    const int64_t tiles = ((N + 127) / 128) * ((M + 127) / 128);
-    return (((tiles + 63) & ~(int64_t)63) + sp * tiles * T128x128k2split::ACC_REGS * (T128x128k2split::WAVES * 64)) * 4;
+    const int64_t tiles = split_tiles(M, N);
+    return (((tiles + 63) & ~(int64_t)63) + sp * tiles * T64x64k4split::ACC_REGS * (T64x64k4split::WAVES * 64)) * 4;
 }
 
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
@@ -564,7 +621,7 @@ hipError_t launch_linear_mfma_ws(const uint8_t *xq, const uint8_t *wq, int64_t M
     const int sp = split_count(M, N, K);
     if (sp < 2 || !ws || ws_bytes < linear_workspace_bytes(M, N, K) || (wsum && K > 65535) || forced_gemm_tile() != 0)
         return launch_linear_mfma(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    return launch_cfg<T128x128k2split>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, sp);
+    return launch_cfg<T64x64k4split>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, sp);
 }
 
 hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
@@ -585,8 +642,8 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;   // the same tile, two workgroups per CU
     typedef GemmCfg<2, 2, 2, 2, 3, 1, 2> T128x128k2;   // 128 x 128 alone on a CU, two K groups
     typedef GemmCfg<2, 2, 4, 2, 3, 1, 2> T256x128k2;   // 256 x 128 alone on a CU, two K groups
-    typedef GemmCfg<2, 2, 1, 1, 3, 2, 2> T64x64k2;     // small tiles with two K groups for problems with few of the
-    typedef GemmCfg<2, 2, 2, 1, 3, 2, 2> T128x64k2;    // larger ones: 64 x 64 and 128 (N) x 64 (M)
+    typedef GemmCfg<1, 1, 2, 2, 4, 1, 4> T64x64k4;     // small tiles for problems with few of the larger ones, four K groups:
+    typedef GemmCfg<2, 1, 2, 2, 3, 1, 4> T128x64k4;    // 64 x 64 with one wave per group, 128 (N) x 64 (M) with two
     // Estimated time in microseconds, fitted to measurements on uniform random operands (the clock is
     // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
     // one-workgroup-per-CU shapes run ceil(tiles / 256) rounds of (fixed + per-K-tile) each.  With two
@@ -610,12 +667,13 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
         // second K group (measured 69 against 72 us on the c2 down projection).  Problems so small that even
         // 128 x 128 tiles give every CU at most one workgroup take that tile: the kernel time is then one
         // workgroup's walk through K and the small tile walks fastest (17 against 25 us at K = 4096).  A deeper
-        // ring does not help there; filling the idle CUs would take a split of K across workgroups.
+        // ring does not help there.
         if (pick == 2 && tiles(256, 128) <= CUS) pick = 5;
         if (tiles(128, 128) <= CUS) pick = 4;
-        // Fewer tiles still: the smallest tile shape that still gives every CU at most one workgroup (measured at
-        // K = 4096, N = 4096: 256 tokens 11 us on 64 x 64 tiles against 17 on 128 x 128; 512 tokens 13 us on
-        // 128 x 64 against 18).
+        // Fewer tiles still: the smallest tile shape that still gives every CU at most one workgroup, as four K
+        // groups whose waves each hold a whole 64 x 64 block of outputs (half the LDS reads per MFMA of a 32 x 32
+        // block).  Measured at K = 4096, N = 4096: 256 tokens 9 us on 64 x 64 tiles against 17 on 128 x 128; 512
+        // tokens 12.5 us on 128 x 64 against 18.
         if (tiles(128, 64) <= CUS) pick = 7;
         if (tiles(64, 64) <= CUS) pick = 6;
     }
@@ -624,8 +682,8 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 4) return launch_cfg<T128x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     if (pick == 5) return launch_cfg<T256x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 6) return launch_cfg<T64x64k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 7) return launch_cfg<T128x64k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 6) return launch_cfg<T64x64k4>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    if (pick == 7) return launch_cfg<T128x64k4>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
 }
 

@@ -48,10 +48,11 @@ def test_host_only_entry_points():
 def test_workspace_size_is_host_arithmetic():
     L = fptq.lib()
     f = L.fptq_linear_workspace_bytes
-    assert f(256, 4096, 14336) == (64 + 4 * 64 * 64 * 256) * 4      # 64 tiles of 128 x 128, four K ranges of 28 K tiles
-    assert f(129, 128, 12288) == (64 + 4 * 2 * 64 * 256) * 4        # 2 tiles: the counters take a full 64-word line
-    assert f(512, 4096, 12288) == (128 + 2 * 128 * 64 * 256) * 4    # 128 tiles leave room for two ranges
-    assert f(256, 4096, 8192) == 0 and f(1024, 4096, 14336) == 0 and f(64, 4096, 14336) == 0 and f(2048, 11008, 4096) == 0
+    assert f(256, 1024, 14336) == (64 + 4 * 64 * 64 * 64) * 4       # 64 tiles of 64 x 64, four K ranges of 28 K tiles
+    assert f(129, 128, 12288) == (64 + 4 * 6 * 64 * 64) * 4         # 6 tiles: the counters take a full 64-word line
+    assert f(512, 1024, 12288) == (128 + 2 * 128 * 64 * 64) * 4     # 128 tiles leave room for two ranges
+    assert f(256, 1024, 6144) == (64 + 3 * 64 * 64 * 64) * 4        # 48 K tiles: three ranges of 16
+    assert f(256, 1024, 4096) == 0 and f(256, 4096, 14336) == 0 and f(64, 1024, 14336) == 0 and f(2048, 11008, 4096) == 0
     assert f(0, 4096, 4096) == -2 and f(256, 4096, -1) == -2
     dummy = ctypes.c_void_p(4096)
     odd = ctypes.c_void_p(4096 + 64)                                  # not 256-byte aligned

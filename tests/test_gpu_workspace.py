@@ -20,9 +20,11 @@ def zero_ws(M, N, K, extra=0):
 def test_workspace_size_rules():
     assert fptq.fptq_linear_workspace_bytes(2048, 11008, 4096) == 0          # enough tiles already
     assert fptq.fptq_linear_workspace_bytes(8, 4096, 4096) == 0              # few-token kernel
-    assert fptq.fptq_linear_workspace_bytes(256, 4096, 8192) == 0            # K too short to split
-    n = fptq.fptq_linear_workspace_bytes(256, 4096, 14336)                   # 64 tiles, 4 ranges of 28 K tiles
-    assert n == (64 + 4 * 64 * 64 * 256) * 4
+    assert fptq.fptq_linear_workspace_bytes(256, 1024, 4096) == 0            # K too short to split
+    assert fptq.fptq_linear_workspace_bytes(256, 4096, 14336) == 0           # a 64 x 64 tile for every CU already
+    n = fptq.fptq_linear_workspace_bytes(256, 1024, 14336)                   # 64 tiles, 4 ranges of 28 K tiles
+    assert n == (64 + 4 * 64 * 64 * 64) * 4
+    assert fptq.fptq_linear_workspace_bytes(256, 2048, 14336) == (128 + 2 * 128 * 64 * 64) * 4
     with pytest.raises(fptq.FptqError):
         fptq.fptq_linear_workspace_bytes(0, 4096, 4096)
 
@@ -41,12 +43,12 @@ def test_split_matches_oracle(oracle, M, N, K):
         y, acc = fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, float(inp.s_a), dev(inp.s_w), ws, want_acc=True)
         assert np.array_equal(acc.cpu().numpy(), ref["acc"])
         assert np.array_equal(host_bits(y), ref["y"])
-    counters = ws[: 4 * (((N + 127) // 128) * ((M + 127) // 128))]
+    counters = ws[: 4 * (((N + 63) // 64) * ((M + 63) // 64))]
     assert int(counters.max()) == 0          # arrival counters are back to zero
 
 
-@pytest.mark.parametrize("M,N,K", [(256, 4096, 12288), (512, 4096, 14336), (1024, 1024, 16384), (129, 6144, 12288), (384, 2050, 12296),
-                                   (300, 5000, 28672)])
+@pytest.mark.parametrize("M,N,K", [(256, 2048, 12288), (512, 1024, 14336), (1024, 512, 16384), (129, 2048, 6144), (384, 1030, 12296),
+                                   (300, 1500, 28672), (256, 1024, 6272)])
 def test_split_equals_unsplit_at_size(M, N, K):
     torch.manual_seed(M + N + K)
     xq = torch.randint(0, 256, (fptq.fptq_packed_bytes(M, K),), dtype=torch.uint8, device="cuda")
@@ -71,7 +73,7 @@ def test_split_equals_unsplit_at_size(M, N, K):
 def test_split_never_reads_a_previous_call_s_partials():
     """The same workspace under alternating inputs: a partial tile left over from the previous call (a stale cache
     line on another XCD, say) would show up as a wrong sum."""
-    M, N, K = 256, 4096, 14336
+    M, N, K = 256, 1024, 14336
     torch.manual_seed(5)
     wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(N, K),), dtype=torch.uint8, device="cuda")
     s_w = torch.rand(N, device="cuda") * 0.015 + 0.005
