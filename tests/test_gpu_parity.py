@@ -161,6 +161,33 @@ def test_linear_worst_case_accumulator(oracle):
     assert torch.all(acc == -56 * K)
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 7, 8, "workspace"])
+def test_largest_k_of_the_widened_accumulator(oracle, tile):
+    """K = 131071, all operands -8 (and a block of +7 weights): 256 * acc = 2^31 - 16384 is the largest value the
+    widened accumulator ever holds; every tile shape, the K groups' exchange and the split over workgroups keep it."""
+    M, N, K = 200, 130, 131071
+    x = np.full((M, K), -8, np.int8)
+    w = np.full((N, K), -8, np.int8)
+    w[5:40] = 7
+    s_w = np.random.default_rng(9).uniform(0.005, 0.02, N).astype(np.float32)
+    xq, wq = fptq.fptq_pack_weights(dev(x)), fptq.fptq_pack_weights(dev(w))
+    want = np.full((M, N), 64 * K, np.int32)
+    want[:, 5:40] = -56 * K
+    if tile == "workspace":
+        nbytes = fptq.fptq_linear_workspace_bytes(M, N, K)
+        assert nbytes > 0
+        ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        y, acc = fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, 0.25, dev(s_w), ws, want_acc=True)
+    else:
+        fptq.fptq_set_gemm_tile(tile)
+        try:
+            y, acc = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.25, dev(s_w), want_acc=True)
+        finally:
+            fptq.fptq_set_gemm_tile(0)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    assert np.array_equal(host_bits(y), oracle.epilogue(want, np.float32(0.25), s_w))
+
+
 @pytest.mark.parametrize("M", [3, 200])
 def test_k_beyond_the_widened_accumulator_limit(oracle, M):
     """K > 131071: 256 * acc no longer fits int32, so both tuned kernels hand over to the simple one.  All operands
