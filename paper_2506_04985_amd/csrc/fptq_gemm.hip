@@ -240,7 +240,7 @@ __device__ inline void finish(v16i (&a)[TNE][TME], const float (&scv)[(TNE * 32 
             if (live && mm < M && nn < N) {
                 uint16_t *dst = y + (int64_t)mm * N + nn;
                 if (ALIGNED) {       // N % 8 == 0: the segment is whole and 16-byte aligned
-                    *reinterpret_cast<uint4 *>(dst) = v;
+                    __builtin_nontemporal_store(v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w}, reinterpret_cast<v4i *>(dst));
                 } else {
                     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -424,6 +424,14 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // K-group shapes serve problems whose whole time is one workgroup's walk through K, and have registers to
+    // spare: the epilogue's channel scales are fetched here, so that their latency hides under the first tile's.
+    const int sub0 = C::KS > 1 ? kg * C::SUBS : 0;                          // first sub-tile of this wave's share of the epilogue
+    const int fin_nw0 = n0 + (wave_n * C::TN + sub0 % C::TN) * 32, fin_mw0 = m0 + (wave_m * C::TM + sub0 / C::TN) * 32;
+    float scv[C::NSC];
+    int32_t zwv[C::NSC];
+    if (C::KS > 1) load_scales<C::TNE>(scv, zwv, s_w, wsum, fin_nw0, N, lane);
+
     const int steps = (max(kt_end - kt_begin, 0) + C::KS - 1) / C::KS;      // the same for every K group: they share the barriers
 #pragma unroll
     for (int s = 0; s < C::STAGES - 1; ++s) {
@@ -491,11 +499,6 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     // after one barrier, adds what the others stored for it.
     if (C::KS > 1) {
         constexpr int P = C::SUBS, TPG = C::WAVES * 64, QUAD_BYTES = TPG * 16;
-        const int tn0 = (kg * P) % C::TN, tm0 = (kg * P) / C::TN;
-        const int nw0 = n0 + (wave_n * C::TN + tn0) * 32;
-        float scv[C::NSC];
-        int32_t zwv[C::NSC];
-        load_scales<C::TNE>(scv, zwv, s_w, wsum, nw0, N, lane);      // in flight during the exchange
         uint8_t *const xlane = lds + (wave * 64 + lane) * 16;
 #pragma unroll
         for (int f = 0; f < C::TN * C::TM; ++f) {
@@ -533,16 +536,12 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         }
         __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_s_barrier();                                // the exchange area is free for the epilogue
-        finish<C, C::TNE, C::TME, ALIGNED, DUMP>(mine, scv, zwv, lds, wave_all, wave, lane, kg * P, nw0,
-                                                 m0 + (wave_m * C::TM + tm0) * 32, M, N, s_a, d, zp, wsum, y, acc_out, ws,
-                                                 splits, split, pid, total);
+        finish<C, C::TNE, C::TME, ALIGNED, DUMP>(mine, scv, zwv, lds, wave_all, wave, lane, sub0, fin_nw0, fin_mw0, M, N, s_a, d,
+                                                 zp, wsum, y, acc_out, ws, splits, split, pid, total);
     } else {
-        const int nw0 = n0 + wave_n * (C::TN * 32);
-        float scv[C::NSC];
-        int32_t zwv[C::NSC];
-        load_scales<C::TN>(scv, zwv, s_w, wsum, nw0, N, lane);
-        finish<C, C::TN, C::TM, ALIGNED, DUMP>(acc, scv, zwv, lds, wave_all, wave, lane, 0, nw0, m0 + wave_m * (C::TM * 32),
-                                               M, N, s_a, d, zp, wsum, y, acc_out, ws, splits, split, pid, total);
+        load_scales<C::TN>(scv, zwv, s_w, wsum, fin_nw0, N, lane);
+        finish<C, C::TN, C::TM, ALIGNED, DUMP>(acc, scv, zwv, lds, wave_all, wave, lane, 0, fin_nw0, fin_mw0, M, N, s_a, d, zp,
+                                               wsum, y, acc_out, ws, splits, split, pid, total);
     }
 }
 

@@ -8,7 +8,9 @@
 //     workgroups fit a CU (no LDS ring, few registers), which overlaps their ramp-up and tails;
 //   - weights go HBM -> registers directly in MFMA operand order: lane (i = l % 16, g = l / 16)
 //     loads granule g (16 bytes, 32 values) of row i, so a wave-level load covers one contiguous
-//     1 KB chunk (16 rows x 64 bytes) and U such loads are in flight per wave;
+//     1 KB chunk (16 rows x 64 bytes) and U such loads are in flight per wave; they are streaming
+//     (non-temporal) loads: every weight byte is used once, and keeping it out of the caches' way
+//     is worth 8 % of the layer time;
 //   - the activations of the same K tile (M x 64 bytes, L2 resident) are loaded the same way,
 //     token rows clamped to M - 1 (duplicate columns are computed and dropped);
 //   - v_mfma_i32_16x16x64_i8 does the arithmetic: A = 16 weight rows, B = 16 tokens (MT B
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(64 * WAVES) void linear_decode_kernel(
             if (base + u < T) {
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt)
-                    wv[rt][u] = *reinterpret_cast<const v4i *>(wp[rt] + (int64_t)(wave + (base + u) * WAVES) * w_slab);
+                    wv[rt][u] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(wp[rt] + (int64_t)(wave + (base + u) * WAVES) * w_slab));
             }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -164,26 +166,27 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
     if (M > 128 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     // Shapes chosen by measurement on the Llama-3-8B matrices (graph replay over cold weights).  16 waves
     // split K whenever there are at least two K tiles per wave: small-N matrices then still put enough
-    // loads in flight on every CU.  Wide matrices (N >= 16384) have workgroups to spare and take more
-    // channels per workgroup with 8 waves, which cuts the activation re-reads; with more than 16
-    // tokens the same holds from N = 6144 on.  The register budget (128 per wave with 16 waves) bounds
+    // loads in flight on every CU, and with the weights on streaming loads one K tile in flight per wave and
+    // more resident workgroups beat deeper unrolling.  Wide matrices (N >= 16384) have workgroups to spare
+    // and take 64 channels per workgroup, which cuts the activation re-reads to a quarter; with more than 16
+    // tokens 32 channels pay from N = 6144 on.  The register budget (128 per wave with 16 waves) bounds
     // RT * MT and the K tiles in flight.
     const bool deep = k_tiles(K) >= 32;
 #define FPTQ_DEC(W, U, MT, RT) return launch_decode_cfg<W, U, MT, RT>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
     if (M <= 16) {
-        if (N >= 16384) FPTQ_DEC(8, 2, 1, 2);
-        if (deep) FPTQ_DEC(16, 4, 1, 1);
+        if (N >= 16384) FPTQ_DEC(16, 1, 1, 4);
+        if (deep) FPTQ_DEC(16, 1, 1, 1);
         FPTQ_DEC(8, 4, 1, 1);
     }
     if (M <= 32) {
-        if (N >= 16384) FPTQ_DEC(8, 2, 2, 2);
-        if (deep && N >= 6144) FPTQ_DEC(16, 4, 2, 2);
-        if (deep) FPTQ_DEC(16, 4, 2, 1);
+        if (N >= 16384) FPTQ_DEC(8, 2, 2, 4);
+        if (deep && N >= 6144) FPTQ_DEC(16, 1, 2, 2);
+        if (deep) FPTQ_DEC(16, 1, 2, 1);
         FPTQ_DEC(8, 4, 2, 1);
     }
     if (M <= 64) {
-        if (N >= 16384) FPTQ_DEC(8, 2, 4, 2);
-        if (deep && N >= 6144) FPTQ_DEC(16, 2, 4, 2);
+        if (N >= 16384) FPTQ_DEC(8, 1, 4, 4);
+        if (deep && N >= 6144) FPTQ_DEC(8, 1, 4, 2);
         if (deep) FPTQ_DEC(16, 2, 4, 1);
         FPTQ_DEC(8, 2, 4, 1);
     }

@@ -64,6 +64,28 @@ def test_quantize_act_bit_exact(oracle, mode, M, K):
             assert np.array_equal(xq.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("M,K,mode", [(16512, 8192, synth.MODE_RMS), (5000, 28672, synth.MODE_GIVEN)])
+def test_quantize_act_larger_than_the_last_level_cache(oracle, M, K, mode):
+    """Inputs above 256 MB take the streaming-load path of both quantizer kernels: sampled rows against the oracle,
+    every row against the same kernel on the two halves of the tensor (each small enough for the ordinary path)."""
+    torch.manual_seed(M)
+    x = (torch.randn((M, K), device="cuda") * 1.5).to(torch.bfloat16)
+    x[:, 7] *= 30.0
+    r_in = (torch.rand(M, device="cuda") + 0.5) if mode == synth.MODE_GIVEN else None
+    xq, r = fptq.fptq_quantize_act(x, 0.4, mode, 1e-5, r_in)
+    q = fptq.fptq_unpack(xq, M, K)
+    h = M // 2
+    for lo, hi in ((0, h), (h, M)):
+        xq2, r2 = fptq.fptq_quantize_act(x[lo:hi].contiguous(), 0.4, mode, 1e-5, None if r_in is None else r_in[lo:hi].contiguous())
+        assert torch.equal(fptq.fptq_unpack(xq2, hi - lo, K), q[lo:hi]) and torch.equal(r2, r[lo:hi])
+    rows = np.random.default_rng(M).choice(M, 48, replace=False)
+    bits = x[torch.from_numpy(rows).cuda()].view(torch.int16).cpu().numpy().view(np.uint16)
+    rin = None if r_in is None else r_in.cpu().numpy()[rows]
+    r_ref = oracle.row_scale(bits, mode, 1e-5, rin)
+    assert np.array_equal(r.cpu().numpy()[rows].view(np.uint32), r_ref.view(np.uint32))
+    assert np.array_equal(q.cpu().numpy()[rows], oracle.quantize(bits, np.float32(0.4), r_ref))
+
+
 def test_quantize_act_special_values(oracle):
     """Ties, clamp edges, infinities, NaN, signed zero, subnormals: same decisions as the oracle."""
     vals = np.array([0.5, 1.5, 2.5, -0.5, -1.5, 7.5, -8.5, 6.5, -7.5, 100.0, -100.0, 0.0, -0.0,
