@@ -136,7 +136,7 @@ int fptq_quantize_act_dynamic(const void *x_bf16, int64_t M, int64_t K, void *xq
 /*
  * The quantized linear layer proper: INT4 x INT4 matmul with INT32 accumulation and the
  * float-scale epilogue (App. J; App. B).  Picks a few-token kernel (bound by the weight read) for
- * M <= 64, and for M <= 128 against fewer than 16384 channels, and the INT8-MFMA GEMM otherwise.
+ * M <= 32, and for M <= 64 against fewer than 10240 channels, and the INT8-MFMA GEMM otherwise.
  *   xq_packed      device, packed activations [M x K] from fptq_quantize_act
  *   w_packed       device, packed weights [N x K] from fptq_pack_weights
  *   s_a            the same static activation scale given to fptq_quantize_act

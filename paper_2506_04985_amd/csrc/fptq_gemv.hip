@@ -1,4 +1,4 @@
-// Few-token (decode) kernel of the quantized linear layer: M <= 128 tokens against packed INT4
+// Few-token (decode) kernel of the quantized linear layer: M <= 64 tokens against packed INT4
 // weights, INT32 accumulation, float-scale epilogue to bf16 (App. J and App. B of the paper).
 //
 // The job is bound by reading the packed weights once from HBM, so the kernel is built around
@@ -19,8 +19,8 @@
 //   - the WAVES partial accumulators are added into one LDS tile with LDS atomics (integers:
 //     exact, order-free).
 // Every workgroup streams all of X, so the activation traffic from L2 grows with M: beyond 32 tokens
-// the kernel is no longer bound by the weights alone, but up to 128 tokens it still beats the prefill
-// kernel, whose 256 x 128 tiles leave most CUs idle at such M.
+// the kernel is no longer bound by the weights alone; up to 64 tokens (32 on wide matrices) it still beats the
+// prefill kernel's smallest tiles.
 #include "fptq_common.h"
 
 namespace fptq {
@@ -162,8 +162,8 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
                                 const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                                     hipStream_t s)
 {
-    // Limits: M <= 128; 256 * acc must stay in int32; the grid is one workgroup per 16 RT channels.
-    if (M > 128 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    // Limits: M <= 64; 256 * acc must stay in int32; the grid is one workgroup per 16 RT channels.
+    if (M > 64 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     // Shapes chosen by measurement on the Llama-3-8B matrices (graph replay over cold weights).  16 waves
     // split K whenever there are at least two K tiles per wave: small-N matrices then still put enough
     // loads in flight on every CU, and with the weights on streaming loads one K tile in flight per wave and
@@ -184,15 +184,10 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
         if (deep) FPTQ_DEC(16, 1, 2, 1);
         FPTQ_DEC(8, 4, 2, 1);
     }
-    if (M <= 64) {
-        if (N >= 16384) FPTQ_DEC(8, 1, 4, 4);
-        if (deep && N >= 6144) FPTQ_DEC(8, 1, 4, 2);
-        if (deep) FPTQ_DEC(16, 2, 4, 1);
-        FPTQ_DEC(8, 2, 4, 1);
-    }
-    if (N >= 6144) FPTQ_DEC(8, 1, 8, 2);
-    if (deep) FPTQ_DEC(16, 1, 8, 1);
-    FPTQ_DEC(8, 1, 8, 1);
+    if (N >= 16384) FPTQ_DEC(8, 1, 4, 4);
+    if (deep && N >= 6144) FPTQ_DEC(8, 1, 4, 2);
+    if (deep) FPTQ_DEC(16, 2, 4, 1);
+    FPTQ_DEC(8, 2, 4, 1);
 #undef FPTQ_DEC
 }
 
