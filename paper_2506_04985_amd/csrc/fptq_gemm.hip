@@ -36,9 +36,9 @@ constexpr int MAX_SPLITS = 4;     // K ranges per output tile in the split-K var
 
 // OCC_ = workgroups meant to share a CU (caps the register budget: 512 / OCC_ per lane).  KS_ = K groups:
 // KS_ sets of WAVES waves work on the same output tile, set g on K tiles g, g + KS_, ..., each with its own
-// LDS ring; their accumulators are added through LDS and every group runs its share of the epilogue.  A problem with at most one
-// workgroup per CU runs one wave per SIMD, which cannot hide its own LDS and VALU latencies; a second K group
-// gives every SIMD a second wave without needing more output tiles.
+// LDS ring; their accumulators are added through LDS and every group runs its share of the epilogue.  A
+// problem with at most one workgroup per CU runs one wave per SIMD, which cannot hide its own LDS and VALU
+// latencies; more K groups give every SIMD more waves without needing more output tiles.
 // SPLIT_: several workgroups share an output tile, each on a contiguous range of K tiles; they leave their
 // partial accumulators in a caller-provided workspace and the last one to arrive adds them and runs the epilogue.
 template <int WAVES_N_, int WAVES_M_, int TN_, int TM_, int STAGES_, int OCC_ = 1, int KS_ = 1, bool SPLIT_ = false>
