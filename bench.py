@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, GB/s
 # FETCH_SIZE and WRITE_SIZE counter passes summarised in profiles/bench_c2_mlp_and_decode.md (reads scaled by
 # 2.0, writes by 1.0, the factors a 1 GiB elementwise add calibrates).  Offline figures: counters cannot be
 # read from inside this script.  The algorithmic bytes are the packed operands, the scales and the bf16 output.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 233.6e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 224.8e6
 GEMM_ALGORITHMIC_BYTES_PER_LAUNCH = 95079424
 
 
