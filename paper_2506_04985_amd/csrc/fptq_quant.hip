@@ -250,6 +250,48 @@ __global__ __launch_bounds__(QT) void quantize_act_dynamic_kernel(const uint16_t
     }
 }
 
+// The same with one workgroup per row (rows of at most 2048 * CH values, K % 8 == 0, 16-byte aligned): a row is
+// spread over four waves, which is faster whenever rows are long or few.
+template <int CH>
+__global__ __launch_bounds__(QT) void quantize_act_dynamic_row_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K,
+                                                                      uint8_t *__restrict__ out, float *__restrict__ s_out)
+{
+    __shared__ uint32_t red[QT / 64];
+    const int64_t t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int64_t Kpad = k_tiles(K) * KT;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)(x + t * K), 0, (int)K * 2, Q_RSRC_FLAGS);
+    q_v4u regs[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) regs[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (i * QT + tid) * 16, 0, 0);
+    uint32_t mx = 0;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) mx = max(mx, max(abs_bits_no_nan(w[j] & 0xffffu), abs_bits_no_nan(w[j] >> 16)));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off, 64));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < QT / 64; ++w) mx = max(mx, red[w]);
+    const float amax = bf16_to_f32(mx);
+    const float s = (amax > 0.0f && mx < 0x7f80u) ? amax / 7.0f : 1.0f;
+    const float c = 1.0f / s;
+    if (tid == 0) s_out[t] = s;
+    uint8_t *orow = out + (((int64_t)(tid >> 4) * M + t) * SEG + (tid & 15) * 4);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        const int k0 = (i * QT + tid) * QCHUNK;
+        const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+        uint32_t word = quant_chunk(w, c, 8);
+        if (k0 >= (int)K) word = 0u;                          // K padding stays zero
+        if (k0 < (int)Kpad) *reinterpret_cast<uint32_t *>(orow + (int64_t)(16 * i) * M * SEG) = word;
+    }
+}
+
 hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, uint8_t *out, float *s_out, hipStream_t s)
 {
     const int64_t blocks = (M + QT / 64 - 1) / (QT / 64);
@@ -257,18 +299,29 @@ hipError_t launch_quantize_act_dynamic(const uint16_t *x, int64_t M, int64_t K, 
     dim3 grid((unsigned)blocks), block(QT);
     const bool vec = K % QCHUNK == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
     const int64_t Kpad = k_tiles(K) * KT;
-#define FPTQ_DYN_CASE(CH)                                                        \
-    if (vec && Kpad <= 512 * CH) {                                               \
-        quantize_act_dynamic_kernel<CH><<<grid, block, 0, s>>>(x, M, K, out, s_out); \
-        return hipGetLastError();                                                \
+    // as for the static quantizer: a wave per row only for many short rows, otherwise a workgroup per row
+    if (vec && Kpad <= 512 * 8 && M > 768) {
+        if (Kpad <= 512 * 4)
+            quantize_act_dynamic_kernel<4><<<grid, block, 0, s>>>(x, M, K, out, s_out);
+        else
+            quantize_act_dynamic_kernel<8><<<grid, block, 0, s>>>(x, M, K, out, s_out);
+        return hipGetLastError();
     }
+    if (M > 0x7fffffff) return hipErrorInvalidValue;
+#define FPTQ_DYN_CASE(CH)                                                                          \
+    if (vec && Kpad <= 2048 * CH) {                                                                \
+        quantize_act_dynamic_row_kernel<CH><<<dim3((unsigned)M), block, 0, s>>>(x, M, K, out, s_out); \
+        return hipGetLastError();                                                                  \
+    }
+    FPTQ_DYN_CASE(1)
+    FPTQ_DYN_CASE(2)
     FPTQ_DYN_CASE(4)
+    FPTQ_DYN_CASE(6)
+    FPTQ_DYN_CASE(7)
     FPTQ_DYN_CASE(8)
     FPTQ_DYN_CASE(12)
+    FPTQ_DYN_CASE(14)
     FPTQ_DYN_CASE(16)
-    FPTQ_DYN_CASE(20)
-    FPTQ_DYN_CASE(22)
-    FPTQ_DYN_CASE(24)
 #undef FPTQ_DYN_CASE
     quantize_act_dynamic_kernel<0><<<grid, block, 0, s>>>(x, M, K, out, s_out);
     return hipGetLastError();
@@ -284,22 +337,15 @@ static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps
     // An input that the 256 MB last-level cache cannot hold is read with streaming loads (8192 x 28672: 119 us
     // against 142); a smaller one is usually still there from its producer, and ordinary loads are faster on it.
     const int stream_in = M * K * 2 > ((int64_t)256 << 20) ? 1 : 0;
-    if (vec && Kpad <= 512 * 24) {
+    // A wave per row pays only for short rows in large numbers (measured crossover at 4096 values: about 1000
+    // rows); otherwise a workgroup per row, which spreads a row over four waves (32 x 11008: 2.9 us against 5.6;
+    // 2048 x 11008: 10.8 against 12.9; 2048 x 4096 the other way, 6.0 against 5.3).
+    if (vec && Kpad <= 512 * 8 && M > 768) {
         dim3 wgrid((unsigned)((M + QT / 64 - 1) / (QT / 64)));
-#define FPTQ_WAVE_CASE(CH)                                                                                                  \
-    if (Kpad <= 512 * CH) {                                                                                                 \
-        quantize_act_wave_kernel<MODE, CH><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out, stream_in);      \
-        return hipGetLastError();                                                                                           \
-    }
-        // chunks per lane: the smallest listed count that covers the row (22 is the Llama-2 FFN width, 21.5 * 512)
-        FPTQ_WAVE_CASE(4)
-        FPTQ_WAVE_CASE(8)
-        FPTQ_WAVE_CASE(12)
-        FPTQ_WAVE_CASE(16)
-        FPTQ_WAVE_CASE(20)
-        FPTQ_WAVE_CASE(22)
-        FPTQ_WAVE_CASE(24)
-#undef FPTQ_WAVE_CASE
+        if (Kpad <= 512 * 4)
+            quantize_act_wave_kernel<MODE, 4><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out, stream_in);
+        else
+            quantize_act_wave_kernel<MODE, 8><<<wgrid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out, stream_in);
         return hipGetLastError();
     }
 #define FPTQ_ROW_CASE(CH)                                                                                                   \
@@ -307,7 +353,11 @@ static hipError_t launch_mode(const uint16_t *x, int64_t M, int64_t K, float eps
         quantize_act_kernel<MODE, CH><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, zoff, out, row_out, stream_in);            \
         return hipGetLastError();                                                                                           \
     }
-    // chunks per thread: 7 and 14 are the Llama-3 FFN widths 14336 and 28672
+    // chunks per thread: 6 covers the Llama-2 FFN width 11008, 7 and 14 are the Llama-3 FFN widths 14336 and 28672
+    FPTQ_ROW_CASE(1)
+    FPTQ_ROW_CASE(2)
+    FPTQ_ROW_CASE(4)
+    FPTQ_ROW_CASE(6)
     FPTQ_ROW_CASE(7)
     FPTQ_ROW_CASE(8)
     FPTQ_ROW_CASE(12)

@@ -12,7 +12,10 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("M,K", [(1, 8), (3, 34), (5, 129), (17, 512), (9, 4096), (4, 11008), (2, 28672), (3, 1001),
-                                 (2, 40000), (300, 640)])
+                                 (2, 40000), (300, 640),
+                                 # every launch shape: a workgroup per row (all widths), a wave per row (many short rows)
+                                 (3, 2048), (5, 8192), (4, 12288), (3, 14336), (2, 16384), (2, 24576), (2, 32768),
+                                 (800, 2048), (1000, 4096), (770, 520)])
 def test_dynamic_quantizer_bit_exact(oracle, M, K):
     rng = np.random.default_rng(M * 5 + K)
     x = rng.standard_normal((M, K)).astype(np.float32) * np.exp(rng.standard_normal((M, 1))).astype(np.float32)

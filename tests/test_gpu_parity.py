@@ -46,7 +46,10 @@ def test_pack_weights_odd_K():
 # ------------------------------------------------------------------ activation quantizer
 @pytest.mark.parametrize("mode", [synth.MODE_NONE, synth.MODE_RMS, synth.MODE_GIVEN])
 @pytest.mark.parametrize("M,K", [(1, 8), (3, 34), (5, 129), (17, 512), (128, 512), (9, 4096), (4, 11008), (2, 28672),
-                                 (2, 40000), (3, 1001)])
+                                 (2, 40000), (3, 1001),
+                                 # every launch shape: a workgroup per row (all widths), a wave per row (many short rows)
+                                 (3, 2048), (5, 8192), (4, 12288), (3, 14336), (2, 16384), (2, 24576), (2, 32768),
+                                 (800, 2048), (1000, 4096), (770, 520)])
 def test_quantize_act_bit_exact(oracle, mode, M, K):
     case = small_case(M, 8, K, mode, seed=M + K)
     inp = synth.draw(case, with_weights=False)
