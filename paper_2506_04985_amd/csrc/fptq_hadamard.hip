@@ -51,11 +51,13 @@ template <int MODE>
 __global__ __launch_bounds__(256) void quantize_act_hadamard_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K,
                                                                     float eps, const float *__restrict__ row_in,
                                                                     float inv_s_a, float hnorm, uint8_t *__restrict__ out,
-                                                                    float *__restrict__ row_out)
+                                                                    float *__restrict__ row_out, int ksplit)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[4 * H_WAVE_LDS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+    // ksplit waves share a row: wave `part` of them takes every ksplit-th group of four blocks
+    const int64_t wid = (int64_t)blockIdx.x * 4 + wave, t = wid / ksplit;
+    const int part = (int)(wid % ksplit);
     if (t >= M) return;                                  // whole waves leave; nothing below synchronises
     const uint16_t *row = x + t * K;
 
@@ -79,13 +81,13 @@ __global__ __launch_bounds__(256) void quantize_act_hadamard_kernel(const uint16
         r = row_in[t];
     }
     const float c = ((MODE == FPTQ_SCALE_NONE) ? inv_s_a : r * inv_s_a) * hnorm;
-    if (lane == 0 && row_out) row_out[t] = r;
+    if (lane == 0 && part == 0 && row_out) row_out[t] = r;
 
     const int b = lane >> 4, g = lane & 15;
     uint8_t *raw = lds + wave * H_WAVE_LDS + b * H_RAW_BLK;
     float *patch = reinterpret_cast<float *>(lds + wave * H_WAVE_LDS + 4 * H_RAW_BLK) + b * H_F32_BLK;
 
-    for (int64_t sc = 0; sc < K; sc += 4 * HB) {
+    for (int64_t sc = (int64_t)part * (4 * HB); sc < K; sc += (int64_t)ksplit * (4 * HB)) {
         const int64_t k0 = sc + b * HB + 16 * g;          // first of this lane's 16 contiguous values
         const bool live = sc + b * HB < K;
         if (live) {
@@ -160,13 +162,14 @@ template <int MODE, int V>
 __global__ __launch_bounds__(256) void quantize_act_hadamard_wide_kernel(const uint16_t *__restrict__ x, int64_t M, int64_t K,
                                                                          float eps, const float *__restrict__ row_in,
                                                                          float inv_s_a, float hnorm, uint8_t *__restrict__ out,
-                                                                         float *__restrict__ row_out)
+                                                                         float *__restrict__ row_out, int ksplit)
 {
     constexpr int B = 64 * V;
     constexpr int WAVE_WORDS = B + 256;          // fp32 patch: 4 pad words after every V elements (64 groups)
     extern __shared__ __attribute__((aligned(16))) uint8_t wide_lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t wid = (int64_t)blockIdx.x * 4 + wave, t = wid / ksplit;     // ksplit waves share a row, block by block
+    const int part = (int)(wid % ksplit);
     if (t >= M) return;                                  // whole waves leave; nothing below synchronises
     const uint16_t *row = x + t * K;
 
@@ -190,12 +193,12 @@ __global__ __launch_bounds__(256) void quantize_act_hadamard_wide_kernel(const u
         r = row_in[t];
     }
     const float c = ((MODE == FPTQ_SCALE_NONE) ? inv_s_a : r * inv_s_a) * hnorm;
-    if (lane == 0 && row_out) row_out[t] = r;
+    if (lane == 0 && part == 0 && row_out) row_out[t] = r;
 
     uint8_t *raw = wide_lds + wave * (WAVE_WORDS * 4);
     float *patch = reinterpret_cast<float *>(raw);
 
-    for (int64_t sc = 0; sc < K; sc += B) {
+    for (int64_t sc = (int64_t)part * B; sc < K; sc += (int64_t)ksplit * B) {
         // linear copy of the block into LDS, 1 KB per wave-level load
 #pragma unroll
         for (int i = 0; i < V / 8; ++i)
@@ -236,11 +239,23 @@ __global__ __launch_bounds__(256) void quantize_act_hadamard_wide_kernel(const u
     }
 }
 
+// Waves per row: with few rows a wave per row leaves the device idle (one token of 11008 values took 9.5 us, as
+// long as 512 tokens), so the blocks of a row are dealt to as many waves as it takes to have about 4096 in all
+// (16384 was slower again: 2048 x 11008 17.1 us against 13.9).
+// In RMS mode every wave of a row sums the whole row again, which only pays while there are few rows.
+static int waves_per_row(int64_t M, int64_t chunks, int mode)
+{
+    if (M >= 4096 || (mode == FPTQ_SCALE_RMS && M > 256)) return 1;
+    const int64_t want = (4096 + M - 1) / M;
+    return (int)(want < chunks ? want : chunks);
+}
+
 template <int V>
 static hipError_t launch_wide(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in, float inv_s_a,
                               uint8_t *out, float *row_out, hipStream_t s)
 {
-    const int64_t blocks = (M + 3) / 4;
+    const int ksplit = waves_per_row(M, (K + 64 * V - 1) / (64 * V), mode);
+    const int64_t blocks = (M * ksplit + 3) / 4;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     constexpr int LDS_BYTES = 4 * (64 * V + 256) * 4;
     const float hnorm = (float)(1.0 / sqrt((double)(64 * V)));
@@ -254,7 +269,7 @@ static hipError_t launch_wide(const uint16_t *x, int64_t M, int64_t K, int mode,
             if (e != hipSuccess) return e;                                                                                 \
             attr_set = true;                                                                                               \
         }                                                                                                                  \
-        kern<<<grid, block, LDS_BYTES, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out);                           \
+        kern<<<grid, block, LDS_BYTES, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out, ksplit);                   \
     } while (0)
     switch (mode) {
     case FPTQ_SCALE_NONE: FPTQ_LAUNCH_WIDE(FPTQ_SCALE_NONE); break;
@@ -276,19 +291,20 @@ hipError_t launch_quantize_act_hadamard(const uint16_t *x, int64_t M, int64_t K,
     case 256: break;
     default: return hipErrorInvalidValue;
     }
-    const int64_t blocks = (M + 3) / 4;
+    const int ksplit = waves_per_row(M, (K + 4 * HB - 1) / (4 * HB), mode);
+    const int64_t blocks = (M * ksplit + 3) / 4;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     const float hnorm = 1.0f / 16.0f;       // 1 / sqrt(256)
     dim3 grid((unsigned)blocks), block(256);
     switch (mode) {
     case FPTQ_SCALE_NONE:
-        quantize_act_hadamard_kernel<FPTQ_SCALE_NONE><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out);
+        quantize_act_hadamard_kernel<FPTQ_SCALE_NONE><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out, ksplit);
         break;
     case FPTQ_SCALE_RMS:
-        quantize_act_hadamard_kernel<FPTQ_SCALE_RMS><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out);
+        quantize_act_hadamard_kernel<FPTQ_SCALE_RMS><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out, ksplit);
         break;
     default:
-        quantize_act_hadamard_kernel<FPTQ_SCALE_GIVEN><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out);
+        quantize_act_hadamard_kernel<FPTQ_SCALE_GIVEN><<<grid, block, 0, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out, ksplit);
     }
     return hipGetLastError();
 }

@@ -21,18 +21,23 @@ __device__ inline uint32_t r_pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, r_bf16x2));
 }
 
-// One wave per row.  CH > 0: K % 8 == 0, K <= 512 * CH, rows 16-byte aligned, z kept in registers.
-// CH == 0: any K, the inputs are read twice (the second time from cache).
-template <int CH>
+// WPR waves per row: 1 (four rows per workgroup; no LDS, no barrier: for many short rows) or 4 (a workgroup per
+// row).  CH > 0: K % 8 == 0, K <= 512 * WPR * CH, rows 16-byte aligned, z kept in registers.
+// CH == 0 (WPR = 1): any K, the inputs are read twice (the second time from cache).
+template <int CH, int WPR>
 __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint16_t *__restrict__ xr, const uint16_t *__restrict__ yb,
                                                                      int64_t M, int64_t K, const float *__restrict__ s_prev,
                                                                      float eps, float inv_s_a, uint16_t *__restrict__ x_next,
                                                                      float *__restrict__ s_next, uint8_t *__restrict__ out)
 {
+    static_assert(WPR == 1 || (WPR == 4 && CH > 0), "a wave or a workgroup per row");
+    __shared__ double red[4];
+    constexpr int S = 64 * WPR;                          // threads per row
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t t = (int64_t)blockIdx.x * 4 + wave;
-    if (t >= M) return;
+    const int h = WPR == 1 ? lane : (int)threadIdx.x;    // this thread's place in its row
+    const int64_t t = WPR == 1 ? (int64_t)blockIdx.x * 4 + wave : (int64_t)blockIdx.x;
+    if (t >= M) return;                                  // WPR = 1: whole waves leave and nothing below synchronises
     const uint16_t *xrow = xr + t * K, *yrow = yb + t * K;
     uint16_t *orow = x_next + t * K;
     const int64_t Kpad = k_tiles(K) * KT;
@@ -45,8 +50,8 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
         r_v4u a[CH > 0 ? CH : 1], b[CH > 0 ? CH : 1];
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            a[i] = __builtin_amdgcn_raw_buffer_load_b128(xs, (i * 64 + lane) * 16, 0, 0);
-            b[i] = __builtin_amdgcn_raw_buffer_load_b128(ys, (i * 64 + lane) * 16, 0, 0);
+            a[i] = __builtin_amdgcn_raw_buffer_load_b128(xs, (i * S + h) * 16, 0, 0);
+            b[i] = __builtin_amdgcn_raw_buffer_load_b128(ys, (i * S + h) * 16, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -67,15 +72,20 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if (WPR > 1) {
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        ss = (red[0] + red[1]) + (red[2] + red[3]);      // the same order in every thread
+    }
     const float inv = (float)(1.0 / sqrt(ss / (double)K + (double)eps));
-    if (lane == 0) s_next[t] = (s_prev ? s_prev[t] : 1.0f) * inv;
+    if (h == 0) s_next[t] = (s_prev ? s_prev[t] : 1.0f) * inv;
     const float c = inv * inv_s_a;
 
     if (CH > 0) {
-        uint8_t *prow = out + (((int64_t)(lane >> 4) * M + t) * SEG + (lane & 15) * 4);
+        uint8_t *prow = out + (((int64_t)(h >> 4) * M + t) * SEG + (h & 15) * 4);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int k0 = (i * 64 + lane) * 8;
+            const int k0 = (i * S + h) * 8;
             uint32_t word = 0, o[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -86,7 +96,7 @@ __global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint1
             word ^= CODE_TO_NIBBLES;
             if (k0 < (int)K) *reinterpret_cast<uint4 *>(orow + k0) = make_uint4(o[0], o[1], o[2], o[3]);
             else word = 0u;                                      // K padding stays zero
-            if (k0 < (int)Kpad) *reinterpret_cast<uint32_t *>(prow + (int64_t)(4 * i) * M * SEG) = word;
+            if (k0 < (int)Kpad) *reinterpret_cast<uint32_t *>(prow + (int64_t)((S / 16) * i) * M * SEG) = word;
         }
     } else {
         for (int64_t k0 = (int64_t)lane * 8; k0 < Kpad; k0 += 512) {
@@ -109,21 +119,32 @@ hipError_t launch_residual_norm_quantize(const uint16_t *xr, const uint16_t *yb,
                                          float eps, float inv_s_a, uint16_t *x_next, float *s_next, uint8_t *out, hipStream_t s)
 {
     const int64_t blocks = (M + 3) / 4;
-    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    dim3 grid((unsigned)blocks), block(256);
+    if (M > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks), rows((unsigned)M), block(256);
     const bool vec = K % 8 == 0 && ((reinterpret_cast<uintptr_t>(xr) | reinterpret_cast<uintptr_t>(yb) |
                                      reinterpret_cast<uintptr_t>(x_next)) & 15) == 0;
+    // As for the plain quantizer: a wave per row for many short rows (2048 x 4096: 10.2 us), otherwise a workgroup per
+    // row, which spreads a row over four waves (32 x 4096: 4.3 us with a wave per row).
+    if (vec && K <= 4096 && M > 768) {
+        if (K <= 2048)
+            residual_norm_quantize_kernel<4, 1><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
+        else
+            residual_norm_quantize_kernel<8, 1><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
+        return hipGetLastError();
+    }
 #define FPTQ_RES_CASE(CH)                                                                                                       \
-    if (vec && K <= 512 * CH) {                                                                                                 \
-        residual_norm_quantize_kernel<CH><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);      \
+    if (vec && K <= 2048 * CH) {                                                                                                \
+        residual_norm_quantize_kernel<CH, 4><<<rows, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);   \
         return hipGetLastError();                                                                                               \
     }
+    FPTQ_RES_CASE(1)
+    FPTQ_RES_CASE(2)
+    FPTQ_RES_CASE(3)
     FPTQ_RES_CASE(4)
+    FPTQ_RES_CASE(6)
     FPTQ_RES_CASE(8)
-    FPTQ_RES_CASE(12)
-    FPTQ_RES_CASE(16)
 #undef FPTQ_RES_CASE
-    residual_norm_quantize_kernel<0><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
+    residual_norm_quantize_kernel<0, 1><<<grid, block, 0, s>>>(xr, yb, M, K, s_prev, eps, inv_s_a, x_next, s_next, out);
     return hipGetLastError();
 }
 

@@ -18,7 +18,9 @@ def case(M, K, mode, seed):
 
 @pytest.mark.parametrize("mode", [synth.MODE_NONE, synth.MODE_RMS, synth.MODE_GIVEN])
 @pytest.mark.parametrize("M,K", [(1, 256), (3, 512), (5, 768), (7, 1024), (4, 1280), (64, 4096), (9, 11008), (3, 14336),
-                                 (2, 28672), (130, 2304)])
+                                 (2, 28672), (130, 2304),
+                                 # rows shared by several waves (few rows), partly (hundreds) and not at all (thousands)
+                                 (300, 11008), (700, 2560), (4100, 1280)])
 def test_hadamard_quantizer_bit_exact(oracle, mode, M, K):
     inp = synth.draw(case(M, K, mode, seed=M * 3 + K), with_weights=False)
     xb = inp.x_bits
@@ -39,7 +41,8 @@ def test_hadamard_quantizer_bit_exact(oracle, mode, M, K):
 @pytest.mark.parametrize("mode", [synth.MODE_NONE, synth.MODE_RMS, synth.MODE_GIVEN])
 @pytest.mark.parametrize("M,K,B", [(1, 512, 512), (5, 1536, 512), (3, 1024, 1024), (6, 3072, 1024), (2, 2048, 2048), (9, 14336, 2048),
                                    (1, 4096, 4096), (7, 28672, 4096), (130, 8192, 4096), (66, 4096, 2048), (37, 4096, 1024),
-                                   (21, 4096, 512), (4, 11008, 256)])
+                                   (21, 4096, 512), (4, 11008, 256), (300, 4096, 512), (4100, 1024, 512), (4097, 2048, 1024),
+                                   (500, 14336, 2048)])
 def test_hadamard_block_sizes_bit_exact(oracle, mode, M, K, B):
     """Every supported block size, including the largest power of two dividing the down-projection widths of the
     Llama-3 shapes (2048 for 14336, 4096 for 28672): same stage order as the definition, so bit-exact."""

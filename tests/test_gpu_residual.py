@@ -12,7 +12,9 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("with_prev", [False, True])
-@pytest.mark.parametrize("M,K", [(1, 8), (3, 34), (5, 129), (17, 512), (9, 4096), (6, 8192), (3, 11008), (130, 1000), (2, 28672)])
+@pytest.mark.parametrize("M,K", [(1, 8), (3, 34), (5, 129), (17, 512), (9, 4096), (6, 8192), (3, 11008), (130, 1000), (2, 28672),
+                                 # every launch shape: a workgroup per row at each width class, a wave per row (many short rows)
+                                 (5, 2048), (4, 5120), (3, 12288), (2, 16384), (800, 2048), (1000, 4096), (770, 520)])
 def test_residual_step_bit_exact(oracle, M, K, with_prev):
     rng = np.random.default_rng(M * 11 + K)
     xb = synth.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32) * np.exp(rng.standard_normal((M, 1))).astype(np.float32))
