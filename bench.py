@@ -419,8 +419,43 @@ def decode_summary(torch, fptq, dev):
             del g
         gbs = tot_b / tot_ms / 1e6
         res[f"M{M}"] = {"layer_us": round(tot_ms * 1e3, 2), "GBps": round(gbs, 1),
-                        "pct_hbm_peak": round(gbs / HBM_PEAK_GBS * 100, 2), "per_matrix": per}
+                        "pct_hbm_peak": round(gbs / HBM_PEAK_GBS * 100, 2), "per_matrix": per,
+                        "layer_with_activation_kernels_us": round(decode_layer_us(torch, fptq, dev, M, layers, weights), 2)}
     return res
+
+
+def decode_layer_us(torch, fptq, dev, M, layers, weights):
+    """The eight launches of one block in their order, the linears on cold weights: residual step -> QKV, quantizer
+    -> O, residual step -> gate+up, Hadamard quantizer (block 2048) -> down.  Attention and the gated activation
+    between them are not part of this library; their outputs are stand-in tensors."""
+    d, f = layers["qkv"][1], layers["down"][1]
+    bf = lambda *shape: torch.randn(shape, device=dev).to(torch.bfloat16)
+    x_res, y_blk, attn, hid = bf(M, d), bf(M, d), bf(M, d), bf(M, f)
+    x_next = torch.empty_like(x_res)
+    s_n, r_out, r_in = (torch.empty(M, dtype=torch.float32, device=dev) for _ in range(3))
+    r_in.fill_(0.8)
+    xq_d = torch.empty(fptq.fptq_packed_bytes(M, d), dtype=torch.uint8, device=dev)
+    xq_f = torch.empty(fptq.fptq_packed_bytes(M, f), dtype=torch.uint8, device=dev)
+    s_w = {n: torch.rand(N, device=dev) * 0.015 + 0.005 for n, (N, K) in layers.items()}
+    y = {n: torch.empty((M, N), dtype=torch.bfloat16, device=dev) for n, (N, K) in layers.items()}
+    state = {"i": 0}
+
+    def lin(name, xq):
+        N, K = layers[name]
+        ws = weights[name]
+        fptq.fptq_w4a4_linear(xq, ws[state["i"] % len(ws)], M, N, K, 0.5, s_w[name], out=y[name])
+
+    def layer():
+        fptq.fptq_residual_norm_quantize(x_res, y_blk, 0.3, None, 1e-5, x_next=x_next, s_next=s_n, out=xq_d)
+        lin("qkv", xq_d)
+        fptq.fptq_quantize_act(attn, 0.3, 2, 1e-5, r_in, out=xq_d, row_scale_out=r_out)
+        lin("o", xq_d)
+        fptq.fptq_residual_norm_quantize(x_res, y_blk, 0.3, s_n, 1e-5, x_next=x_next, s_next=s_n, out=xq_d)
+        lin("gate_up", xq_d)
+        fptq.fptq_quantize_act_hadamard(hid, 0.3, 2048, 2, 1e-5, r_in, out=xq_f, row_scale_out=r_out)
+        lin("down", xq_f)
+        state["i"] += 1
+    return graph_time_us(torch, layer, iters=12, replays=3)
 
 
 if __name__ == "__main__":
