@@ -647,27 +647,30 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
     // one-workgroup-per-CU shapes run ceil(tiles / 256) rounds of (fixed + per-K-tile) each.  With two
     // workgroups per CU the older one is served first, so epilogues overlap the other's main loop and
-    // a partial last round of r * 512 tiles costs about 0.5 + 0.15 r of a full one instead of 1.
+    // a partial last round of r * 512 tiles costs about 0.5 + 0.15 r of a full one instead of 1; a partial
+    // only round with more tiles than CUs runs at the pace of the CUs that hold two (0.88 of a full round
+    // measured at r = 0.6).  At most one 256 x 128 tile per CU: the two-K-group variant, whose K tiles go
+    // faster the fewer CUs are busy (0.67 us at 256 tiles, 0.55 at 160: the power limit again).
     auto tiles = [&](int64_t bn, int64_t bm) { return (double)(((N + bn - 1) / bn) * ((M + bm - 1) / bm)); };
     const double kt = (double)k_tiles(K), CUS = 256.0;
-    const double x = tiles(256, 128) / (2 * CUS), frac = x - floor(x);
-    const double rounds_o2 = floor(x) + (frac > 0 ? fmax(frac, 0.5 + 0.15 * frac) : 0.0);
-    const double cost[4] = {
+    const double t21 = tiles(256, 128), x = t21 / (2 * CUS), frac = x - floor(x);
+    const double rounds_o2 = x < 1.0 ? 0.7 + 0.3 * x : floor(x) + (frac > 0 ? fmax(frac, 0.5 + 0.15 * frac) : 0.0);
+    const double never = 1e30;
+    const double cost[5] = {
         ceil(tiles(256, 256) / CUS) * (12.9 + 1.235 * kt),
         ceil(tiles(192, 256) / CUS) * (11.0 + 0.900 * kt),
-        ceil(tiles(256, 128) / CUS) * (9.4 + 0.667 * kt),
-        rounds_o2 * (7.8 + 1.304 * kt),
+        t21 > CUS ? ceil(t21 / CUS) * (9.4 + 0.667 * kt) : never,
+        t21 > CUS ? rounds_o2 * (7.8 + 1.304 * kt) : never,
+        t21 <= CUS ? 8.5 + (0.35 + 0.32 * t21 / CUS) * kt : never,
     };
     int pick = g_forced_tile > 0 ? g_forced_tile - 1 : 0;
     if (g_forced_tile <= 0) {
-        for (int i = 1; i < 4; ++i)
+        for (int i = 1; i < 5; ++i)
             if (cost[i] < cost[pick]) pick = i;
-        // At most one workgroup per CU: one wave per SIMD cannot hide its own latencies, so the tile gets a
-        // second K group (measured 69 against 72 us on the c2 down projection).  Problems so small that even
-        // 128 x 128 tiles give every CU at most one workgroup take that tile: the kernel time is then one
-        // workgroup's walk through K and the small tile walks fastest (17 against 25 us at K = 4096).  A deeper
-        // ring does not help there.
-        if (pick == 2 && tiles(256, 128) <= CUS) pick = 5;
+        if (pick == 4) pick = 5;       // the launch table below: 4 = 128 x 128, 5 = 256 x 128, both with two K groups
+        // Problems so small that even 128 x 128 tiles give every CU at most one workgroup take that tile: the
+        // kernel time is then one workgroup's walk through K and the small tile walks fastest (17 against 25 us at
+        // K = 4096).  A deeper ring does not help there.
         if (tiles(128, 128) <= CUS) pick = 4;
         // Fewer tiles still: the smallest tile shape that still gives every CU at most one workgroup, as four K
         // groups whose waves each hold a whole 64 x 64 block of outputs (half the LDS reads per MFMA of a 32 x 32
