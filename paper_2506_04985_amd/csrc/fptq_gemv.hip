@@ -164,27 +164,28 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
 {
     // Limits: M <= 64; 256 * acc must stay in int32; the grid is one workgroup per 16 RT channels.
     if (M > 64 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    // Shapes chosen by measurement on the Llama-3-8B matrices (graph replay over cold weights).  16 waves
-    // split K whenever there are at least two K tiles per wave: small-N matrices then still put enough
-    // loads in flight on every CU, and with the weights on streaming loads one K tile in flight per wave and
-    // more resident workgroups beat deeper unrolling.  Wide matrices (N >= 16384) have workgroups to spare
-    // and take 64 channels per workgroup, which cuts the activation re-reads to a quarter; with more than 16
-    // tokens 32 channels pay from N = 6144 on.  The register budget (128 per wave with 16 waves) bounds
-    // RT * MT and the K tiles in flight.
-    const bool deep = k_tiles(K) >= 32;
+    // Shapes chosen by measurement (graph replay over cold weights) on the linear layers of Llama-2-7B/13B,
+    // Llama-3-8B/70B and Qwen2-7B: 45 matrices times 1, 16 and 32 tokens, 14 shapes each.  16 waves split K
+    // whenever there is at least one K tile per wave: small-N matrices then still put enough loads in flight
+    // on every CU, and with the weights on streaming loads one K tile in flight per wave and more resident
+    // workgroups beat deeper unrolling (except for very long K against few channels).  Up to 4096 channels a
+    // workgroup takes 16 of them, beyond that 32, which halves the activation re-reads; with more than 16
+    // tokens, 64 from 10240 channels on.  Each choice is within about 10 % of the best shape of its case.
+    const int64_t kt = k_tiles(K);
+    const bool deep = kt >= 16;          // at least one K tile for each of 16 waves
 #define FPTQ_DEC(W, U, MT, RT) return launch_decode_cfg<W, U, MT, RT>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
     if (M <= 16) {
-        if (N >= 16384) FPTQ_DEC(16, 1, 1, 4);
-        if (deep) FPTQ_DEC(16, 1, 1, 1);
-        FPTQ_DEC(8, 4, 1, 1);
+        if (!deep) FPTQ_DEC(8, 4, 1, 1);
+        if (N <= 4096 && kt >= 80) FPTQ_DEC(16, 2, 1, 1);
+        if (N <= 4096) FPTQ_DEC(16, 1, 1, 1);
+        FPTQ_DEC(16, 1, 1, 2);
     }
     if (M <= 32) {
-        if (N >= 16384) FPTQ_DEC(8, 2, 2, 4);
-        if (deep && N >= 6144) FPTQ_DEC(16, 1, 2, 2);
-        if (deep) FPTQ_DEC(16, 1, 2, 1);
-        FPTQ_DEC(8, 4, 2, 1);
+        if (!deep) FPTQ_DEC(8, 4, 2, 1);
+        if (N <= 4096) FPTQ_DEC(16, 1, 2, 1);
+        if (N < 10240) FPTQ_DEC(16, 1, 2, 2);
+        FPTQ_DEC(8, 1, 2, 4);
     }
-    if (N >= 16384) FPTQ_DEC(8, 1, 4, 4);
     if (deep && N >= 6144) FPTQ_DEC(8, 1, 4, 2);
     if (deep) FPTQ_DEC(16, 2, 4, 1);
     FPTQ_DEC(8, 2, 4, 1);
