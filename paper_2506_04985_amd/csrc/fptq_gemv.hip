@@ -186,9 +186,10 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
         if (N < 10240) FPTQ_DEC(16, 1, 2, 2);
         FPTQ_DEC(8, 1, 2, 4);
     }
-    if (deep && N >= 6144) FPTQ_DEC(8, 1, 4, 2);
-    if (deep) FPTQ_DEC(16, 2, 4, 1);
-    FPTQ_DEC(8, 2, 4, 1);
+    if (!deep) FPTQ_DEC(8, 2, 4, 1);
+    if (N <= 4096) FPTQ_DEC(16, 2, 4, 1);
+    if (M <= 48) FPTQ_DEC(16, 1, 4, 2);
+    FPTQ_DEC(8, 1, 4, 2);
 #undef FPTQ_DEC
 }
 

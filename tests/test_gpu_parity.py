@@ -118,7 +118,7 @@ SHAPES = [(1, 1, 2), (3, 5, 34), (128, 512, 512), (100, 300, 640), (257, 513, 10
           (32, 16400, 256), (20, 16390, 384), (3, 70, 8200),
           # 33 .. 64 tokens: every launch shape of the few-token kernel (narrow matrices) and the hand-over to the
           # prefill kernel's small tiles (wide ones, and everything from 65 tokens on)
-          (64, 10200, 256), (50, 6200, 4096), (48, 100, 4096), (40, 3000, 4096), (64, 16400, 256), (33, 10240, 384),
+          (64, 10200, 256), (50, 6200, 4096), (48, 100, 4096), (40, 3000, 4096), (40, 5000, 2048), (64, 16400, 256), (33, 10240, 384),
           (128, 16400, 256), (100, 6150, 640), (127, 300, 4224), (65, 200, 4100), (129, 300, 640)]
 
 
