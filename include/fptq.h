@@ -14,8 +14,10 @@
  *
  * Conventions
  *   - Plain C ABI.  Every tensor pointer is a DEVICE pointer; scalars are passed by value.
- *   - The caller owns all memory.  Entry points without "_static" in their name allocate nothing,
- *     never synchronise, and enqueue their kernels on `stream` (a hipStream_t; NULL = the null stream).
+ *   - The caller owns all memory.  Entry points allocate nothing, never synchronise, and enqueue their
+ *     kernels on `stream` (a hipStream_t; NULL = the null stream).  They can be captured into a HIP graph
+ *     (kernel launches only, no memset or copy nodes); call each shape once outside the capture first,
+ *     because the first launch of some kernels sets a function attribute.
  *   - Every function returns 0 (FPTQ_OK) or a negative FPTQ_ERR_* code; arguments are validated
  *     before anything is launched, so a failed call writes nothing.  fptq_last_error() returns a
  *     thread-local description of the last failure.
