@@ -232,6 +232,21 @@ def test_k_beyond_the_widened_accumulator_limit(oracle, M):
     assert np.array_equal(host_bits(y), oracle.epilogue(acc_ref.astype(np.int32), np.float32(0.25), s_w))
 
 
+@pytest.mark.parametrize("M,N,K", [((1 << 24) + 3, 3, 6), (2, (1 << 24) + 5, 4)])
+def test_dimension_beyond_16_million(oracle, M, N, K):
+    """More than 2^24 rows (beyond the prefill kernel's buffer descriptors: the simple kernel answers) and more
+    than 2^24 channels against two tokens (the few-token kernel's 64-bit addressing)."""
+    rng = np.random.default_rng(N)
+    x = rng.integers(-8, 8, (M, K), dtype=np.int8)
+    w = rng.integers(-8, 8, (N, K), dtype=np.int8)
+    s_w = rng.uniform(0.005, 0.02, N).astype(np.float32)
+    xq, wq = fptq.fptq_pack_weights(dev(x)), fptq.fptq_pack_weights(dev(w))
+    y, acc = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.25, dev(s_w), want_acc=True)
+    want = (x.astype(np.int32) @ w.astype(np.int32).T).astype(np.int32)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    assert np.array_equal(host_bits(y), oracle.epilogue(want, np.float32(0.25), s_w))
+
+
 def test_linear_is_deterministic():
     inp = synth.draw(small_case(300, 520, 2048, synth.MODE_RMS, seed=5))
     a = run_gpu_linear(inp)
