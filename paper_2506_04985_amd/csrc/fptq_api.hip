@@ -47,8 +47,9 @@ static int check_align(const char *fn, const void *p, unsigned a, const char *na
 // The few-token kernel serves M <= 32 and, for matrices of fewer than 10240 channels, M <= 64; above that, or
 // whenever a prefill tile shape is forced, the MFMA GEMM runs: its 64 x 64 and 128 x 64 tiles with four K groups
 // are faster from 65 tokens on everywhere, and from 33 tokens on wide matrices (measured over cold weights at 64
-// tokens: 6144 x 4096 7.2 us against 9.4, 4096 x 14336 14.1 against 19.7, but 10240 x 8192 20.4 against 15.5 and
-// 28672 x 4096 19.2 against 14.5; at 80 tokens 4096 x 14336 22.1 against 17.0).
+// tokens, best few-token launch shape against the MFMA kernel: 6144 x 4096 7.0 us against 9.1, 4096 x 14336 13.9
+// against 19.5, but 28672 x 4096 19.1 against 15.9 and 22016 x 4096 16.7 against 14.4, with 10240 to 15360
+// channels about even; at 80 tokens 4096 x 14336 22.1 against 17.0).
 static bool few_token_shape(int64_t M, int64_t N) { return M <= 32 || (M <= 64 && N < 10240); }
 
 typedef hipError_t (*linear_fn)(const uint8_t *, const uint8_t *, int64_t, int64_t, int64_t, float, const float *,
