@@ -93,6 +93,27 @@ def test_config2_llama2_7b_mlp(oracle, idx):
     run_case(oracle, synth.config_cases("c2")[idx], full_acc=True)
 
 
+def test_config2_gate_and_up_as_one_launch(oracle):
+    """The launch the benchmark times: gate and up weights concatenated along N (22016 x 4096), one call; the two
+    halves of Y are the gate and the up output."""
+    gate, up, _ = synth.config_cases("c2")
+    inp = synth.draw(gate, with_weights=False)
+    (w_g, s_g), (w_u, s_u) = synth.draw_weights(gate), synth.draw_weights(up)
+    w, s_w = np.concatenate([w_g, w_u], axis=0), np.concatenate([s_g, s_u])
+    M, N, K = gate.M, gate.N + up.N, gate.K
+    xq, r = fptq.fptq_quantize_act(dev_bf16(inp.x_bits), float(inp.s_a), gate.mode, gate.eps, None)
+    y, acc = fptq.fptq_w4a4_linear(xq, fptq.fptq_pack_weights(dev(w)), M, N, K, float(inp.s_a), dev(s_w), want_acc=True)
+    r_ref = oracle.row_scale(inp.x_bits, gate.mode, gate.eps, None)
+    q_ref = oracle.quantize(inp.x_bits, inp.s_a, r_ref)
+    acc_ref = oracle.gemm_i32(q_ref, w)
+    acc_h = acc.cpu().numpy()
+    assert np.array_equal(acc_h, acc_ref)
+    assert np.array_equal(host_bits(y), oracle.epilogue(acc_ref, inp.s_a, s_w))
+    # the halves are what the two separate launches give
+    y_g = fptq.fptq_w4a4_linear(xq, fptq.fptq_pack_weights(dev(w_g)), M, gate.N, K, float(inp.s_a), dev(s_g))
+    assert torch.equal(y[:, :gate.N].contiguous().view(torch.int16), y_g.view(torch.int16))
+
+
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
 def test_config3_llama3_8b_layer(oracle, idx):
     run_case(oracle, synth.config_cases("c3")[idx], full_acc=True)
