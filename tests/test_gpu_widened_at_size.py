@@ -1,0 +1,64 @@
+"""The widened rows at the sizes the benchmark times (Llama-2-7B and Llama-3-8B activation tensors): the GPU runs
+the whole tensor; the oracle, whose operations are row-local, runs a sample of rows (the first and last tiles of
+rows and a random draw), and those rows must agree bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_04985_amd import binding as fptq
+from paper_2506_04985_amd import synth
+
+from gpu_util import dev, dev_bf16, host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def draw(M, K, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K)).astype(np.float32) * np.exp(0.5 * rng.standard_normal((M, 1))).astype(np.float32)
+    x[:, rng.choice(K, K // 100, replace=False)] *= 20.0
+    rows = np.unique(np.concatenate([np.arange(8), np.arange(M - 8, M), rng.choice(M, 48, replace=False)]))
+    return synth.f32_to_bf16_bits(x), rows, rng
+
+
+@pytest.mark.parametrize("M,K,B", [(2048, 11008, 256), (4096, 14336, 2048), (4096, 14336, 256), (1024, 28672, 4096)])
+def test_hadamard_quantizer_at_size(oracle, M, K, B):
+    xb, rows, rng = draw(M, K, M + K + B)
+    r_in = rng.uniform(0.5, 1.5, M).astype(np.float32)
+    xq, r = fptq.fptq_quantize_act_hadamard(dev_bf16(xb), 0.35, B, synth.MODE_GIVEN, 0.0, dev(r_in))
+    q = fptq.fptq_unpack(xq, M, K).cpu().numpy()
+    assert np.array_equal(q[rows], oracle.quantize_hadamard(xb[rows], np.float32(0.35), B, r_in[rows]))
+    assert np.array_equal(r.cpu().numpy(), r_in)
+    assert q.min() == -8 and q.max() == 7
+
+
+@pytest.mark.parametrize("M,K", [(2048, 11008), (2048, 4096), (4096, 14336)])
+def test_dynamic_quantizer_at_size(oracle, M, K):
+    xb, rows, _ = draw(M, K, M + K + 1)
+    xq, s = fptq.fptq_quantize_act_dynamic(dev_bf16(xb))
+    q = fptq.fptq_unpack(xq, M, K).cpu().numpy()
+    q_ref, s_ref = oracle.quantize_dynamic(xb[rows])
+    assert np.array_equal(q[rows], q_ref)
+    assert np.array_equal(s.cpu().numpy()[rows].view(np.uint32), s_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("M,K", [(2048, 4096), (4096, 8192), (512, 5120)])
+def test_residual_step_at_size(oracle, M, K):
+    xb, rows, rng = draw(M, K, M + K + 2)
+    yb = synth.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32) * 0.5)
+    s_prev = rng.uniform(0.5, 2.0, M).astype(np.float32)
+    x_next, s_next, xq = fptq.fptq_residual_norm_quantize(dev_bf16(xb), dev_bf16(yb), 0.3, dev(s_prev), 1e-5)
+    ref = oracle.residual_norm_quantize(xb[rows], yb[rows], np.float32(0.3), s_prev[rows], 1e-5)
+    assert np.array_equal(fptq.fptq_unpack(xq, M, K).cpu().numpy()[rows], ref["q"])
+    assert np.array_equal(host_bits(x_next)[rows], ref["x_next"])
+    assert np.array_equal(s_next.cpu().numpy()[rows].view(np.uint32), ref["s_next"].view(np.uint32))
+
+
+@pytest.mark.parametrize("M,K,z", [(2048, 11008, 3), (2048, 4096, -5)])
+def test_asymmetric_quantizer_at_size(oracle, M, K, z):
+    xb, rows, _ = draw(M, K, M + K + 3)
+    xq, r = fptq.fptq_quantize_act_asym(dev_bf16(xb), 0.4, z, synth.MODE_RMS, 1e-5)
+    q = fptq.fptq_unpack(xq, M, K).cpu().numpy()
+    r_ref = oracle.row_scale(xb[rows], synth.MODE_RMS, 1e-5, None)
+    assert np.array_equal(r.cpu().numpy()[rows].view(np.uint32), r_ref.view(np.uint32))
+    assert np.array_equal(q[rows], oracle.quantize_zp(xb[rows], np.float32(0.4), z, r_ref))
