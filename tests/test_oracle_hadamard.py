@@ -100,3 +100,63 @@ def test_quantize_hadamard_uses_the_scalar_rule_on_the_transformed_row(oracle):
     xb = synth.f32_to_bf16_bits(x)
     hq = oracle.quantize_hadamard(xb, np.float32(1.0), B)
     assert np.abs(hq).max() <= 8 and (hq != 0).mean() > 0.5
+
+
+def _f32_nearest(fr):
+    """Correctly rounded (nearest, ties to even) float32 of a positive normal-range rational, in exact arithmetic."""
+    from fractions import Fraction
+    e = 0
+    while Fraction(2) ** (e + 1) <= fr:
+        e += 1
+    while Fraction(2) ** e > fr:
+        e -= 1
+    m = round(fr / Fraction(2) ** (e - 23))          # Python rounds a Fraction half to even
+    return float(np.float32(float(Fraction(m) * Fraction(2) ** (e - 23))))
+
+
+def _f32_inv_sqrt(B):
+    """The float32 nearest to 1 / sqrt(B), found without any floating-point square root: f is the nearest float32
+    iff the real value lies between the midpoints to its neighbours, i.e. lo^2 * B < 1 < hi^2 * B in rationals."""
+    from fractions import Fraction
+    f = np.float32(1.0)
+    while Fraction(float(f)) ** 2 * B > 1:            # walk down to the binade below 1 / sqrt(B) ...
+        f = np.float32(f / 2)
+    lo, hi = f, np.float32(f * 2)
+    while np.nextafter(lo, np.float32(2)) < hi:       # ... then bisect on float32 values, comparing exactly
+        mid = np.float32((float(lo) + float(hi)) / 2)
+        if Fraction(float(mid)) ** 2 * B > 1:
+            hi = mid
+        else:
+            lo = mid
+    below, above = Fraction(float(lo)), Fraction(float(hi))
+    midpoint = (below + above) / 2
+    pick = hi if midpoint ** 2 * B < 1 else lo
+    # the bracket that makes `pick` the nearest float32
+    up, dn = np.nextafter(pick, np.float32(2)), np.nextafter(pick, np.float32(0))
+    assert ((Fraction(float(pick)) + Fraction(float(dn))) / 2) ** 2 * B < 1 < ((Fraction(float(pick)) + Fraction(float(up))) / 2) ** 2 * B
+    return float(pick)
+
+
+@pytest.mark.parametrize("B", [8, 32, 128, 256, 512, 1024, 2048, 4096])
+def test_hadamard_multiplier_rounding_and_product_order(oracle, B):
+    """c_t = (S_t * (1 / s_a)) * float32(1 / sqrt(B)): the normalisation is the correctly rounded float32 of the
+    irrational 1 / sqrt(B) for odd powers of two (512, 2048: the Llama-3-8B block), and the two products are taken in
+    that order, each rounded to float32 once.  Everything on the expected side is exact rational arithmetic."""
+    from fractions import Fraction
+    L = oracle.lib()
+    hn = _f32_inv_sqrt(B)
+    rng = np.random.default_rng(B)
+    order_matters = 0
+    for _ in range(200):
+        r = float(np.float32(rng.uniform(0.05, 20.0)))
+        s_a = float(np.float32(rng.uniform(0.01, 3.0)))
+        inv = _f32_nearest(Fraction(1) / Fraction(s_a))
+        c1 = _f32_nearest(Fraction(r) * Fraction(inv))
+        want = _f32_nearest(Fraction(c1) * Fraction(hn))
+        assert L.oracle_hadamard_multiplier(r, s_a, 1, B) == want
+        other = _f32_nearest(Fraction(r) * Fraction(_f32_nearest(Fraction(inv) * Fraction(hn))))
+        order_matters += other != want
+        # without a row scale the first product is skipped
+        assert L.oracle_hadamard_multiplier(123.0, s_a, 0, B) == _f32_nearest(Fraction(inv) * Fraction(hn))
+    if B in (512, 2048, 8, 32, 128):
+        assert order_matters > 0          # the pin can tell the two association orders apart

@@ -237,3 +237,31 @@ def test_up_down_scaler_is_function_preserving_also_with_the_hadamard():
     assert np.abs((h @ Td) @ T.merge_hadamard_down(Wd2, 32) - want).max() <= 1e-12 * np.abs(want).max()
     Wg_bad = Wg * u[None, :]                                 # the gate goes through a nonlinearity: not mergeable there
     assert np.abs(T.gated_mlp(x, Wg_bad, Wu, Wd2) - want).max() > 1e-3 * np.abs(want).max()
+
+
+def test_static_scale_lp_against_exhaustive_search_over_levels():
+    """App. D range setting by brute force on tiny vectors: for every candidate scale the quantized value of an entry is,
+    by definition, the nearest of the 16 levels s * {-8 .. 7}; the error is the sum of cubed distances; all in exact
+    rationals, every candidate tried.  Also the closed-form case: data lying on the min-max grid keep the min-max scale."""
+    from fractions import Fraction
+    rng = np.random.default_rng(77)
+    for trial in range(6):
+        n = 160 if trial % 2 else int(rng.integers(3, 9))
+        x = [Fraction(int(v), 64) for v in rng.integers(-400, 401, n)]
+        if trial % 2:
+            x[0] = Fraction(int(rng.integers(700, 900)), 64)            # an outlier worth clipping among 159 small values
+        n_grid = 40
+        s_max = max(abs(v) for v in x) / 7
+        best, best_err = None, None
+        for i in range(1, n_grid + 1):
+            s = s_max * i / n_grid
+            err = sum(min(abs(v - s * q) for q in range(-8, 8)) ** 3 for v in x)
+            if best_err is None or err < best_err:
+                best, best_err = s, err
+        got = T.static_scale_lp(np.array([float(v) for v in x]), 3.0, n_grid)
+        assert got == np.float32(float(best)), (trial, got, float(best))
+        if trial % 2:
+            assert best < s_max                                            # the outlier is clipped
+    # points on the grid of the min-max scale, both ends used: zero error there and nowhere else among the candidates
+    g = np.array([-7, -3, 0, 1, 5, 7, 2, -6], np.float64) * 0.375
+    assert T.static_scale_lp(g, 3.0) == np.float32(0.375)
