@@ -60,7 +60,7 @@ def main():
         sys.exit(2)
     import torch
     from paper_2506_04985_amd import binding as fptq
-    from paper_2506_04985_amd import synth
+    import fptq_workloads as synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

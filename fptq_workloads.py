@@ -1,7 +1,9 @@
 """Seeded synthetic inputs for the W4A4 linear layer: shapes and value distributions of the
 five benchmark configurations.  This module only draws inputs (activations, integer weights,
-scales); none of the layer's arithmetic lives here, so both the HIP library's tests and the
-CPU checker can be fed from it.
+scales) and belongs to neither the HIP library's package nor the CPU checker: the tests and the
+benchmark feed both from it, and neither of the two imports it.  The one statistic it computes,
+the calibration constant s_a, is an input like the others (a float64 NumPy absmax over a separate
+draw), not a step of the layer.
 
 Activations are returned as bf16 bit patterns (uint16), weights as int8 in [-8, 7] (one value
 per element, [N, K] = [out, in]), weight scales as float32 [N].  The static activation scale

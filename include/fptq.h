@@ -16,13 +16,16 @@
  *   - Plain C ABI.  Every tensor pointer is a DEVICE pointer; scalars are passed by value.
  *   - The caller owns all memory.  Entry points allocate nothing, never synchronise, and enqueue their
  *     kernels on `stream` (a hipStream_t; NULL = the null stream).  They can be captured into a HIP graph
- *     (kernel launches only, no memset or copy nodes); call each shape once outside the capture first,
- *     because the first launch of some kernels sets a function attribute.
+ *     (kernel launches only, no memset or copy nodes).  The first call on a device sets that device up (kernel
+ *     attributes, device properties); call fptq_init() on the device, or any entry point, before capturing.
+ *     Entry points may be called from several threads and on several devices (the current device is used).
  *   - Every function returns 0 (FPTQ_OK) or a negative FPTQ_ERR_* code; arguments are validated
  *     before anything is launched, so a failed call writes nothing.  fptq_last_error() returns a
  *     thread-local description of the last failure.
  *   - X is [M x K] bf16 row-major (tokens x in-features).  W is [N x K] (out x in).  Y is [M x N]
- *     bf16 row-major.  Any M, N, K >= 1 is accepted (M*K, N*K, M*N < 2^40).
+ *     bf16 row-major.  Any M, N, K >= 1 is accepted (M*K, N*K, M*N < 2^40); the linear entry points also need
+ *     K <= 2^25 - 1 (K <= 2^24 - 1 with a zero point), the longest sums for which INT32 accumulation is exact,
+ *     and return FPTQ_ERR_SHAPE beyond that.
  *
  * Packed INT4 layout (the same for activations and weights, produced only by this library):
  *   K is cut into tiles of 128 values (64 bytes); the buffer holds, tile after tile, one 64-byte
@@ -57,6 +60,10 @@ extern "C" {
 
 int fptq_version(void);
 const char *fptq_last_error(void);
+
+/* Optional: set the current device up now (otherwise the first call that launches on it does).  Idempotent,
+ * thread-safe; call it once per device before capturing entry points into a HIP graph. */
+int fptq_init(void);
 
 /* Bytes of a packed [rows x K] INT4 buffer in the library layout; negative FPTQ_ERR_SHAPE if
  * rows < 1 or K < 1. */
@@ -191,28 +198,6 @@ int fptq_w4a4_linear_ws(const void *xq_packed, const void *w_packed, int64_t M, 
  * the tuned kernels at full size. */
 int fptq_w4a4_linear_ref(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
                          const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream);
-
-/* Testing / tuning knob for the prefill kernel's tile shape (process-wide, not thread-safe against
- * concurrent fptq_w4a4_linear calls): 0 = chosen per problem (default), 1 = 256x256, 2 = 192 (N) x
- * 256 (M), 3 = 256 (N) x 128 (M), 4 = 256 x 128 with two workgroups per CU, 5 = 128 x 128 and
- * 6 = 256 x 128 with two K groups per workgroup, 7 = 64 x 64 and 8 = 128 (N) x 64 (M) with four K groups.
- * A forced shape also sends calls with few tokens to the prefill kernel.  Results do not depend on it. */
-int fptq_set_gemm_tile(int tile);
-
-/*
- * Measurement aids (not part of the method): loops with nothing but the resource being measured, so a
- * benchmark can report the rate the device sustains next to the kernels' own, from the same run.
- *
- * fptq_probe_mfma_rate: 256 workgroups of 4 waves, each wave issuing iters x 64 v_mfma_i32_32x32x32_i8 on
- *   register operands (dense = 0: all zero; otherwise random nibbles in the high half of every byte, the
- *   operand form of the prefill kernel).  out: device, 65536 int32, receives a checksum per thread.
- *   Returns the number of integer operations launched (> 0), or a negative FPTQ_ERR_* code.  The caller
- *   times the launch.
- * fptq_probe_read: streams `bytes` (a multiple of 16; src 16-byte aligned) once and XORs all 16-byte words
- *   into xor4 (device, 4 int32, which the caller zeroes first), component by component.
- */
-int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream);
-int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream);
 
 /* Library layout -> one int8 per value, [rows x K] row-major (for parity checks and debugging). */
 int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream);

@@ -1,0 +1,42 @@
+/*
+ * fptq_probe -- measurement aids for benchmarks of the fptq library on AMD MI355X (gfx950).  Not part of the
+ * quantized linear layer and not linked into libfptq.so: loops with nothing but the resource being measured, so a
+ * benchmark can report the rate the device sustains next to the kernels' own, from the same run.
+ *
+ * Plain C ABI, device pointers, kernels enqueued on `stream` (a hipStream_t; NULL = the null stream), nothing
+ * allocated, nothing synchronised.  Errors are negative; fptq_probe_last_error() describes the last one of the thread.
+ */
+#ifndef FPTQ_PROBE_H
+#define FPTQ_PROBE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FPTQ_PROBE_ERR_NULL (-1)
+#define FPTQ_PROBE_ERR_SHAPE (-2)
+#define FPTQ_PROBE_ERR_HIP (-5)
+#define FPTQ_PROBE_ERR_VALUE (-6)
+
+const char *fptq_probe_last_error(void);
+
+/*
+ * 256 workgroups of 4 waves, each wave issuing iters x 64 v_mfma_i32_32x32x32_i8 on register operands (dense = 0:
+ * all zero; otherwise random nibbles in the high half of every byte, the operand form of the prefill kernel).
+ *   out  device, 65536 int32: receives a checksum per thread.
+ * Returns the number of integer operations launched (> 0) or a negative error.  The caller times the launch.
+ */
+int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream);
+
+/*
+ * Streams `bytes` (a multiple of 16; src 16-byte aligned) once and XORs all 16-byte words into xor4 (device,
+ * 4 int32, which the caller zeroes first), component by component.
+ */
+int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FPTQ_PROBE_H */

@@ -15,12 +15,12 @@ SCALE_NONE, SCALE_RMS, SCALE_GIVEN = 0, 1, 2
 ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4: "FPTQ_ERR_MODE",
              -5: "FPTQ_ERR_HIP", -6: "FPTQ_ERR_VALUE", -7: "FPTQ_ERR_ALIGN"}
 
-# every symbol include/fptq.h declares
-EXPORTS = ["fptq_version", "fptq_last_error", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
+# every symbol include/fptq.h declares, and the test knob of include/fptq_testing.h
+EXPORTS = ["fptq_version", "fptq_last_error", "fptq_init", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
            "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic", "fptq_quantize_act_asym",
            "fptq_weight_row_sums", "fptq_w4a4_linear_zp", "fptq_residual_norm_quantize",
-           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_set_gemm_tile",
-           "fptq_probe_mfma_rate", "fptq_probe_read", "fptq_linear_workspace_bytes", "fptq_w4a4_linear_ws"]
+           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_linear_workspace_bytes", "fptq_w4a4_linear_ws"]
+TESTING_EXPORTS = ["fptq_set_gemm_tile"]
 
 _lib = None
 
@@ -41,6 +41,7 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         i64, f32, p, i32 = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_int
         L.fptq_version.restype = i32
+        L.fptq_init.restype = i32
         L.fptq_last_error.restype = ctypes.c_char_p
         L.fptq_packed_bytes.restype = i64
         L.fptq_packed_bytes.argtypes = [i64, i64]
@@ -71,10 +72,6 @@ def lib():
         L.fptq_linear_workspace_bytes.argtypes = [i64, i64, i64]
         L.fptq_w4a4_linear_ws.restype = i32
         L.fptq_w4a4_linear_ws.argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p, i64, p]
-        L.fptq_probe_mfma_rate.restype = i64
-        L.fptq_probe_mfma_rate.argtypes = [i32, i32, p, p]
-        L.fptq_probe_read.restype = i32
-        L.fptq_probe_read.argtypes = [p, i64, p, p]
         _lib = L
     return _lib
 
@@ -100,6 +97,11 @@ def _dev(t, dtype, name):
 
 def fptq_version():
     return lib().fptq_version()
+
+
+def fptq_init():
+    """Set the current device up (kernel attributes, device properties); the first launching call does it otherwise."""
+    _check(lib().fptq_init())
 
 
 def fptq_packed_bytes(rows, K):
@@ -262,22 +264,3 @@ def fptq_unpack(packed, rows, K):
     out = torch.empty((rows, K), dtype=torch.int8, device=packed.device)
     _check(lib().fptq_unpack(_ptr(packed), rows, K, _ptr(out), _stream()))
     return out
-
-
-def fptq_probe_mfma_rate(iters, dense, out=None):
-    """Launch the MFMA-only loop; returns (integer operations launched, per-thread checksums).  The caller times it."""
-    out = torch.empty(65536, dtype=torch.int32, device="cuda") if out is None else out
-    _dev(out, torch.int32, "out")
-    ops = lib().fptq_probe_mfma_rate(int(iters), int(bool(dense)), _ptr(out), _stream())
-    if ops < 0:
-        _check(int(ops))
-    return int(ops), out
-
-
-def fptq_probe_read(src, xor4=None):
-    """Stream a device buffer once; returns the XOR of its 16-byte words as 4 int32 (xor4 is zeroed here if not given)."""
-    if not src.is_cuda or not src.is_contiguous():
-        raise TypeError("src must be a contiguous CUDA tensor")
-    xor4 = torch.zeros(4, dtype=torch.int32, device=src.device) if xor4 is None else xor4
-    _check(lib().fptq_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(xor4), _stream()))
-    return xor4

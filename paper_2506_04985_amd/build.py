@@ -1,5 +1,5 @@
-"""Compile the HIP sources under csrc/ for gfx950 into csrc/libfptq.so (in-tree, so that the
-built library travels with the source tree)."""
+"""Compile the HIP sources under csrc/ for gfx950 into csrc/libfptq.so, and the measurement aids into
+csrc/libfptq_probe.so (in-tree, so that the built libraries travel with the source tree)."""
 import os
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
@@ -8,7 +8,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(CSRC, "libfptq.so")
-SOURCES = ["fptq_api.hip", "fptq_pack.hip", "fptq_quant.hip", "fptq_gemm.hip", "fptq_gemv.hip", "fptq_hadamard.hip", "fptq_residual.hip", "fptq_probe.hip"]
+PROBE_LIB = os.path.join(CSRC, "libfptq_probe.so")
+SOURCES = ["fptq_api.hip", "fptq_pack.hip", "fptq_quant.hip", "fptq_gemm.hip", "fptq_gemv.hip", "fptq_hadamard.hip", "fptq_residual.hip"]
+PROBE_SOURCES = ["fptq_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -27,13 +29,15 @@ def _compile(src):
 
 
 def build(verbose: bool = False) -> str:
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        results = list(ex.map(_compile, SOURCES))
+    with ThreadPoolExecutor(max_workers=len(SOURCES) + len(PROBE_SOURCES)) as ex:
+        results = list(ex.map(_compile, SOURCES + PROBE_SOURCES))
     if verbose:
         for _, out in results:
             if out.strip():
                 print(out)
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *[o for o, _ in results], "-o", LIB])
+    objs = [o for o, _ in results]
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs[:len(SOURCES)], "-o", LIB])
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs[len(SOURCES):], "-o", PROBE_LIB])
     return LIB
 
 

@@ -3,8 +3,10 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "fptq_common.h"
+#include "fptq_testing.h"
 
 namespace fptq {
 
@@ -25,6 +27,48 @@ static int hip_fail(const char *what, hipError_t e)
 }
 
 static const int64_t MAX_ELEMS = (int64_t)1 << 40;
+// INT32 accumulation is exact while 64 K < 2^31 (|q w| <= 64); with a zero point the epilogue forms
+// acc - z * sum_k w, at most 128 K in magnitude.
+static const int64_t MAX_K = ((int64_t)1 << 25) - 1, MAX_K_ZERO_POINT = ((int64_t)1 << 24) - 1;
+
+// ---- per-device state.  Filled once per device under a lock; readers take the lock-free path afterwards.
+static DeviceInfo g_devices[MAX_DEVICES];
+static std::atomic<bool> g_device_ready[MAX_DEVICES];
+static std::mutex g_device_mutex;
+
+hipError_t device_info(const DeviceInfo **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!g_device_ready[dev].load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(g_device_mutex);
+        if (!g_device_ready[dev].load(std::memory_order_relaxed)) {
+            DeviceInfo info = {};
+            info.device = dev;
+            int cus = 0;
+            if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+            info.cus = cus > 0 ? cus : DEFAULT_CUS;
+            if ((e = gemm_device_init(&info)) != hipSuccess) return e;
+            if ((e = hadamard_device_init(dev)) != hipSuccess) return e;
+            g_devices[dev] = info;
+            g_device_ready[dev].store(true, std::memory_order_release);
+        }
+    }
+    *out = &g_devices[dev];
+    return hipSuccess;
+}
+
+int device_cus_or_default()
+{
+    const DeviceInfo *info;
+    if (device_info(&info) != hipSuccess) {
+        (void)hipGetLastError();     // a host-only query without a device must not leave a sticky error behind
+        return DEFAULT_CUS;
+    }
+    return info->cus;
+}
 
 static int check_dims(const char *fn, int64_t a, int64_t b, const char *an, const char *bn)
 {
@@ -80,6 +124,11 @@ static int linear_common(const char *fn, linear_fn force, const void *xq, const 
         set_error("%s: zero_point must be in [-8, 7] and needs w_row_sum", fn);
         return FPTQ_ERR_VALUE;
     }
+    if (K > (zp != 0 ? MAX_K_ZERO_POINT : MAX_K)) {
+        set_error("%s: K=%lld exceeds %lld, the longest sum INT32 holds exactly%s", fn, (long long)K,
+                  (long long)(zp != 0 ? MAX_K_ZERO_POINT : MAX_K), zp != 0 ? " with a zero point" : "");
+        return FPTQ_ERR_SHAPE;
+    }
     if (zp == 0) wsum = nullptr;
     if ((rc = check_align(fn, workspace, 256, "workspace"))) return rc;
     if (workspace_bytes < 0) {
@@ -102,7 +151,14 @@ using namespace fptq;
 
 extern "C" {
 
-int fptq_version(void) { return 100; }
+int fptq_version(void) { return 200; }
+
+int fptq_init(void)
+{
+    const DeviceInfo *info;
+    hipError_t e = device_info(&info);
+    return e == hipSuccess ? FPTQ_OK : hip_fail("fptq_init", e);
+}
 
 const char *fptq_last_error(void) { return g_err; }
 
@@ -294,6 +350,10 @@ int64_t fptq_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
     int rc;
     if ((rc = check_dims(fn, M, K, "M", "K")) || (rc = check_dims(fn, N, K, "N", "K")) || (rc = check_dims(fn, M, N, "M", "N")))
         return rc;
+    if (K > MAX_K) {
+        set_error("%s: K=%lld exceeds %lld, the longest sum INT32 holds exactly", fn, (long long)K, (long long)MAX_K);
+        return FPTQ_ERR_SHAPE;
+    }
     return few_token_shape(M, N) ? 0 : linear_workspace_bytes(M, N, K);
 }
 
@@ -313,42 +373,6 @@ int fptq_set_gemm_tile(int tile)
     }
     set_gemm_tile(tile);
     return FPTQ_OK;
-}
-
-int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream)
-{
-    const char *fn = "fptq_probe_mfma_rate";
-    if (!out) {
-        set_error("%s: NULL pointer", fn);
-        return FPTQ_ERR_NULL;
-    }
-    if (iters < 1 || iters > (1 << 20)) {
-        set_error("%s: iters must be in [1, 2^20]", fn);
-        return FPTQ_ERR_VALUE;
-    }
-    int rc = check_align(fn, out, 4, "out");
-    if (rc) return rc;
-    hipError_t e = launch_probe_mfma(iters, dense != 0, out, (hipStream_t)stream);
-    if (e != hipSuccess) return hip_fail(fn, e);
-    // workgroups x waves x iterations x MFMAs per iteration x operations of one 32x32x32 MFMA
-    return (int64_t)PROBE_MFMA_WORKGROUPS * 4 * iters * 64 * (2 * 32 * 32 * 32);
-}
-
-int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream)
-{
-    const char *fn = "fptq_probe_read";
-    if (!src || !xor4) {
-        set_error("%s: NULL pointer", fn);
-        return FPTQ_ERR_NULL;
-    }
-    if (bytes < 16 || bytes % 16 != 0) {
-        set_error("%s: bytes must be a positive multiple of 16 (got %lld)", fn, (long long)bytes);
-        return FPTQ_ERR_SHAPE;
-    }
-    int rc;
-    if ((rc = check_align(fn, src, 16, "src")) || (rc = check_align(fn, xor4, 4, "xor4"))) return rc;
-    hipError_t e = launch_probe_read(src, bytes, xor4, (hipStream_t)stream);
-    return e == hipSuccess ? FPTQ_OK : hip_fail(fn, e);
 }
 
 int fptq_unpack(const void *packed, int64_t rows, int64_t K, int8_t *out_int8, void *stream)

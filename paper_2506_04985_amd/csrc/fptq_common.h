@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "fptq.h"
 
 namespace fptq {
@@ -49,10 +51,30 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
 void set_gemm_tile(int tile);
 int forced_gemm_tile();
 
-// measurement aids (fptq_probe.hip): one workgroup of four waves per CU of the device
-constexpr int PROBE_MFMA_WORKGROUPS = 256;
-hipError_t launch_probe_mfma(int iters, int dense, int32_t *out, hipStream_t s);
-hipError_t launch_probe_read(const void *src, int64_t bytes, int32_t *xor4, hipStream_t s);
+// Per-device state, set up once per device (by fptq_init or by the first call that needs it; thread-safe):
+// the number of compute units, which the launchers size their grids and pick their tile shapes by.
+constexpr int MAX_DEVICES = 64;
+constexpr int DEFAULT_CUS = 256;                 // MI355X; used by the host-only size queries when no device answers
+struct DeviceInfo {
+    int device;
+    int cus;
+};
+hipError_t device_info(const DeviceInfo **out);  // state of the current device
+int device_cus_or_default();                     // compute units of the current device, DEFAULT_CUS without one
+// what each translation unit contributes to that set-up (called with the device current, under the set-up lock)
+hipError_t gemm_device_init(DeviceInfo *info);
+hipError_t hadamard_device_init(int device);
+
+// Once-per-device guard for a kernel's function attribute: bit d of `done` is set when device d has it.
+// Setting it twice is harmless, so a race between two first callers needs no lock.
+#define FPTQ_ONCE_PER_DEVICE(done, device, call)                                             \
+    do {                                                                                     \
+        if (!((done).load(std::memory_order_acquire) >> (device) & 1)) {                     \
+            hipError_t e_ = (call);                                                          \
+            if (e_ != hipSuccess) return e_;                                                 \
+            (done).fetch_or((uint64_t)1 << (device), std::memory_order_release);            \
+        }                                                                                    \
+    } while (0)
 
 // fp32 -> bf16 bit pattern, round to nearest even (NaN stays a quiet NaN)
 __device__ inline uint16_t bf16_rne(float f)

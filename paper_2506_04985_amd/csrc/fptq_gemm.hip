@@ -545,23 +545,20 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     }
 }
 
-// 0 = choose the tile shape per problem; 1..4 = force one (testing and tuning)
-static int g_forced_tile = 0;
-void set_gemm_tile(int tile) { g_forced_tile = tile; }
-int forced_gemm_tile() { return g_forced_tile; }
+// 0 = choose the tile shape per problem; 1..8 = force one (testing and tuning)
+static std::atomic<int> g_forced_tile{0};
+void set_gemm_tile(int tile) { g_forced_tile.store(tile, std::memory_order_relaxed); }
+int forced_gemm_tile() { return g_forced_tile.load(std::memory_order_relaxed); }
 
 template <class C, bool ALIGNED, bool DUMP>
 static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                               const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                               hipStream_t s, int32_t *ws = nullptr, int splits = 1)
 {
-    static bool attr_set = false;
     auto kern = linear_mfma_kernel<C, ALIGNED, DUMP>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    const DeviceInfo *info;
+    hipError_t e0 = device_info(&info);          // sets every instantiation's LDS attribute on the device's first use
+    if (e0 != hipSuccess) return e0;
     int64_t tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     if (tiles_m * tiles_n * splits > 0x7fffffff) return hipErrorInvalidValue;
     kern<<<dim3((unsigned)(tiles_m * tiles_n * splits)), dim3(C::THREADS), C::LDS_BYTES, s>>>(
@@ -581,19 +578,60 @@ static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, in
                    : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits);
 }
 
-// ---- split K over workgroups, for problems whose 64 x 64 tiles cover at most half of the CUs.
+// ---- tile shapes (all with 4 waves per K group).  The 256 x 256 tile has the best operand reuse and wins for long
+// K; 256 x 128 with two workgroups per CU hides prologue and epilogue and fills partial rounds, and wins elsewhere;
+// the 192- and one-workgroup 128-row shapes are kept for shapes neither fits; the K-group shapes serve problems with
+// at most one workgroup per CU.
+typedef GemmCfg<2, 2, 4, 4, 4> T256x256;           // waves of 128 x 128
+typedef GemmCfg<2, 2, 3, 4, 4> T192x256;           // BN = 192: waves of 96 (n) x 128 (m)
+typedef GemmCfg<2, 2, 4, 2, 4> T256x128;           // BM = 128: waves of 128 (n) x 64 (m)
+typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;      // the same tile, two workgroups per CU
+typedef GemmCfg<2, 2, 2, 2, 3, 1, 2> T128x128k2;   // 128 x 128 alone on a CU, two K groups
+typedef GemmCfg<2, 2, 4, 2, 3, 1, 2> T256x128k2;   // 256 x 128 alone on a CU, two K groups
+typedef GemmCfg<1, 1, 2, 2, 4, 1, 4> T64x64k4;     // small tiles for problems with few of the larger ones, four K groups:
+typedef GemmCfg<2, 1, 2, 2, 3, 1, 4> T128x64k4;    // 64 x 64 with one wave per group, 128 (N) x 64 (M) with two
+// split K over workgroups, for problems whose 64 x 64 tiles cover at most half of the CUs
 typedef GemmCfg<1, 1, 2, 2, 4, 1, 4, true> T64x64k4split;
+
+template <class C, bool ALIGNED, bool DUMP>
+static hipError_t set_lds_attribute()
+{
+    return hipFuncSetAttribute((const void *)linear_mfma_kernel<C, ALIGNED, DUMP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               C::LDS_BYTES);
+}
+
+template <class... Cs>
+static hipError_t set_lds_attributes()
+{
+    hipError_t e = hipSuccess;
+    auto one = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+    (void)one;
+    ((one(set_lds_attribute<Cs, true, true>()), one(set_lds_attribute<Cs, true, false>()), one(set_lds_attribute<Cs, false, true>()),
+      one(set_lds_attribute<Cs, false, false>())),
+     ...);
+    return e;
+}
+
+// Once per device, with that device current: every kernel instantiation gets its dynamic-LDS limit (so no launch
+// has to set it later, e.g. under graph capture).
+hipError_t gemm_device_init(DeviceInfo *info)
+{
+    hipError_t e = set_lds_attributes<T256x256, T192x256, T256x128, T256x128o2, T128x128k2, T256x128k2, T64x64k4, T128x64k4,
+                                      T64x64k4split>();
+    (void)info;
+    return e;
+}
 
 // Number of K ranges: as many as keep the workgroup count within the CUs, at most MAX_SPLITS, at least 16 K tiles
 // (four per K group) each, none empty.  The exchange of partials pays from K = 6144 on (measured on N = 1024,
 // M = 256: K = 4096 takes 8.0 us unsplit and 8.6 split, K = 6144 9.8 and 9.0, K = 14336 16.6 and 11.4, K = 28672
 // 28.3 and 16.7).
 static int64_t split_tiles(int64_t M, int64_t N) { return ((N + T64x64k4split::BN - 1) / T64x64k4split::BN) * ((M + T64x64k4split::BM - 1) / T64x64k4split::BM); }
-static int split_count(int64_t M, int64_t N, int64_t K)
+static int split_count(int64_t M, int64_t N, int64_t K, int cus)
 {
     const int64_t tiles = split_tiles(M, N), kt = k_tiles(K);
-    if (tiles > 128 || K > 131071 || kt < 48) return 1;
-    int64_t sp = 256 / tiles;
+    if (tiles > cus / 2 || K > 131071 || kt < 48) return 1;
+    int64_t sp = cus / tiles;
     if (sp > kt / 16) sp = kt / 16;
     if (sp > MAX_SPLITS) sp = MAX_SPLITS;
     if (sp < 2) return 1;
@@ -603,21 +641,17 @@ static int split_count(int64_t M, int64_t N, int64_t K)
 
 int64_t linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    const int sp = split_count(M, N, K);
+    const int sp = split_count(M, N, K, device_cus_or_default());
     if (sp < 2) return 0;
     const int64_t tiles = split_tiles(M, N);
     return (((tiles + 63) & ~(int64_t)63) + sp * tiles * T64x64k4split::ACC_REGS * (T64x64k4split::WAVES * 64)) * 4;
 }
 
-hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
-                              hipStream_t s);
-
 hipError_t launch_linear_mfma_ws(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                                  const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                                  int32_t *ws, int64_t ws_bytes, hipStream_t s)
 {
-    const int sp = split_count(M, N, K);
+    const int sp = split_count(M, N, K, device_cus_or_default());
     if (sp < 2 || !ws || ws_bytes < linear_workspace_bytes(M, N, K) || (wsum && K > 65535) || forced_gemm_tile() != 0)
         return launch_linear_mfma(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
     return launch_cfg<T64x64k4split>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, sp);
@@ -631,28 +665,16 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     // of all rows (rows * 64 bytes) must fit a 32-bit buffer descriptor.  Beyond them the simple
     // kernel answers.
     if (K > 131071 || (wsum && K > 65535) || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    // Tile shapes (all 4 waves).  The 256 x 256 tile has the best operand reuse and wins for long K;
-    // 256 x 128 with two workgroups per CU hides prologue and epilogue and fills partial rounds, and
-    // wins elsewhere; the 192- and one-workgroup 128-row shapes are kept for shapes neither fits; the
-    // two-K-group shapes serve problems with at most one workgroup per CU.
-    typedef GemmCfg<2, 2, 4, 4, 4> T256x256;   // waves of 128 x 128
-    typedef GemmCfg<2, 2, 3, 4, 4> T192x256;   // BN = 192: waves of 96 (n) x 128 (m)
-    typedef GemmCfg<2, 2, 4, 2, 4> T256x128;   // BM = 128: waves of 128 (n) x 64 (m)
-    typedef GemmCfg<2, 2, 4, 2, 3, 2> T256x128o2;   // the same tile, two workgroups per CU
-    typedef GemmCfg<2, 2, 2, 2, 3, 1, 2> T128x128k2;   // 128 x 128 alone on a CU, two K groups
-    typedef GemmCfg<2, 2, 4, 2, 3, 1, 2> T256x128k2;   // 256 x 128 alone on a CU, two K groups
-    typedef GemmCfg<1, 1, 2, 2, 4, 1, 4> T64x64k4;     // small tiles for problems with few of the larger ones, four K groups:
-    typedef GemmCfg<2, 1, 2, 2, 3, 1, 4> T128x64k4;    // 64 x 64 with one wave per group, 128 (N) x 64 (M) with two
-    // Estimated time in microseconds, fitted to measurements on uniform random operands (the clock is
+    // Estimated time in microseconds, fitted to measurements on uniform random operands on MI355X (the clock is
     // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
-    // one-workgroup-per-CU shapes run ceil(tiles / 256) rounds of (fixed + per-K-tile) each.  With two
+    // one-workgroup-per-CU shapes run ceil(tiles / CUs) rounds of (fixed + per-K-tile) each.  With two
     // workgroups per CU the older one is served first, so epilogues overlap the other's main loop and
-    // a partial last round of r * 512 tiles costs about 0.5 + 0.15 r of a full one instead of 1; a partial
+    // a partial last round of r * 2 CUs tiles costs about 0.5 + 0.15 r of a full one instead of 1; a partial
     // only round with more tiles than CUs runs at the pace of the CUs that hold two (0.88 of a full round
     // measured at r = 0.6).  At most one 256 x 128 tile per CU: the two-K-group variant, whose K tiles go
     // faster the fewer CUs are busy (0.67 us at 256 tiles, 0.55 at 160: the power limit again).
     auto tiles = [&](int64_t bn, int64_t bm) { return (double)(((N + bn - 1) / bn) * ((M + bm - 1) / bm)); };
-    const double kt = (double)k_tiles(K), CUS = 256.0;
+    const double kt = (double)k_tiles(K), CUS = (double)device_cus_or_default();
     const double t21 = tiles(256, 128), x = t21 / (2 * CUS), frac = x - floor(x);
     const double rounds_o2 = x < 1.0 ? 0.7 + 0.3 * x : floor(x) + (frac > 0 ? fmax(frac, 0.5 + 0.15 * frac) : 0.0);
     const double never = 1e30;
@@ -663,8 +685,9 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
         t21 > CUS ? rounds_o2 * (7.8 + 1.304 * kt) : never,
         t21 <= CUS ? 8.5 + (0.35 + 0.32 * t21 / CUS) * kt : never,
     };
-    int pick = g_forced_tile > 0 ? g_forced_tile - 1 : 0;
-    if (g_forced_tile <= 0) {
+    const int forced = forced_gemm_tile();
+    int pick = forced > 0 ? forced - 1 : 0;
+    if (forced <= 0) {
         for (int i = 1; i < 5; ++i)
             if (cost[i] < cost[pick]) pick = i;
         if (pick == 4) pick = 5;       // the launch table below: 4 = 128 x 128, 5 = 256 x 128, both with two K groups

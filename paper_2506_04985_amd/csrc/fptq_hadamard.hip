@@ -250,6 +250,30 @@ static int waves_per_row(int64_t M, int64_t chunks, int mode)
     return (int)(want < chunks ? want : chunks);
 }
 
+constexpr int wide_lds_bytes(int v) { return 4 * (64 * v + 256) * 4; }
+
+template <int MODE, int V>
+static hipError_t set_wide_attribute()
+{
+    if (wide_lds_bytes(V) <= 65536) return hipSuccess;
+    return hipFuncSetAttribute((const void *)quantize_act_hadamard_wide_kernel<MODE, V>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               wide_lds_bytes(V));
+}
+
+// Once per device: more than 64 KB of dynamic LDS has to be asked for before the first launch.
+hipError_t hadamard_device_init(int)
+{
+    hipError_t e = hipSuccess;
+    auto one = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+#define FPTQ_WIDE_ATTR(V) one(set_wide_attribute<FPTQ_SCALE_NONE, V>()), one(set_wide_attribute<FPTQ_SCALE_RMS, V>()), one(set_wide_attribute<FPTQ_SCALE_GIVEN, V>())
+    FPTQ_WIDE_ATTR(8);
+    FPTQ_WIDE_ATTR(16);
+    FPTQ_WIDE_ATTR(32);
+    FPTQ_WIDE_ATTR(64);
+#undef FPTQ_WIDE_ATTR
+    return e;
+}
+
 template <int V>
 static hipError_t launch_wide(const uint16_t *x, int64_t M, int64_t K, int mode, float eps, const float *row_in, float inv_s_a,
                               uint8_t *out, float *row_out, hipStream_t s)
@@ -257,18 +281,15 @@ static hipError_t launch_wide(const uint16_t *x, int64_t M, int64_t K, int mode,
     const int ksplit = waves_per_row(M, (K + 64 * V - 1) / (64 * V), mode);
     const int64_t blocks = (M * ksplit + 3) / 4;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    constexpr int LDS_BYTES = 4 * (64 * V + 256) * 4;
+    constexpr int LDS_BYTES = wide_lds_bytes(V);
+    const DeviceInfo *info;
+    hipError_t e0 = device_info(&info);       // the kernels that need more than 64 KB of dynamic LDS got their limit there
+    if (e0 != hipSuccess) return e0;
     const float hnorm = (float)(1.0 / sqrt((double)(64 * V)));
     dim3 grid((unsigned)blocks), block(256);
 #define FPTQ_LAUNCH_WIDE(MODE)                                                                                             \
     do {                                                                                                                   \
         auto kern = quantize_act_hadamard_wide_kernel<MODE, V>;                                                            \
-        static bool attr_set = false; /* more than 64 KB of dynamic LDS has to be asked for once */                         \
-        if (LDS_BYTES > 65536 && !attr_set) {                                                                              \
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
-            if (e != hipSuccess) return e;                                                                                 \
-            attr_set = true;                                                                                               \
-        }                                                                                                                  \
         kern<<<grid, block, LDS_BYTES, s>>>(x, M, K, eps, row_in, inv_s_a, hnorm, out, row_out, ksplit);                   \
     } while (0)
     switch (mode) {

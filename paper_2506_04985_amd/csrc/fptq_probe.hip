@@ -1,9 +1,19 @@
 // Measurement aids: what the matrix pipe and the memory system of the device sustain for loops with
 // nothing else in them, so that a benchmark can put the kernels' rates next to the attainable ones
-// measured on the same device in the same run.  Nothing here is part of the quantized linear layer.
-#include "fptq_common.h"
+// measured on the same device in the same run.  Nothing here is part of the quantized linear layer:
+// this file is built into a shared object of its own (libfptq_probe.so, include/fptq_probe.h) that
+// only the benchmark and its test load.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace fptq {
+#include <cstdio>
+
+#include "fptq_probe.h"
+
+namespace fptq_probe {
+
+constexpr int PROBE_MFMA_WORKGROUPS = 256;       // one workgroup of four waves per CU of an MI355X
+static thread_local char g_err[160] = "";
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -80,18 +90,54 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const v4i *__restrict__
     }
 }
 
-hipError_t launch_probe_mfma(int iters, int dense, int32_t *out, hipStream_t s)
+}  // namespace fptq_probe
+
+using namespace fptq_probe;
+
+extern "C" {
+
+const char *fptq_probe_last_error(void) { return g_err; }
+
+int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream)
 {
-    probe_mfma_kernel<<<dim3(PROBE_MFMA_WORKGROUPS), dim3(256), 0, s>>>(iters, dense, out);
-    return hipGetLastError();
+    if (!out) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate: NULL pointer");
+        return FPTQ_PROBE_ERR_NULL;
+    }
+    if (iters < 1 || iters > (1 << 20)) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate: iters must be in [1, 2^20]");
+        return FPTQ_PROBE_ERR_VALUE;
+    }
+    probe_mfma_kernel<<<dim3(PROBE_MFMA_WORKGROUPS), dim3(256), 0, (hipStream_t)stream>>>(iters, dense != 0, out);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate: %s", hipGetErrorString(e));
+        return FPTQ_PROBE_ERR_HIP;
+    }
+    // workgroups x waves x iterations x MFMAs per iteration x operations of one 32x32x32 MFMA
+    return (int64_t)PROBE_MFMA_WORKGROUPS * 4 * iters * 64 * (2 * 32 * 32 * 32);
 }
 
-hipError_t launch_probe_read(const void *src, int64_t bytes, int32_t *xor4, hipStream_t s)
+int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream)
 {
+    if (!src || !xor4) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_read: NULL pointer");
+        return FPTQ_PROBE_ERR_NULL;
+    }
+    if (bytes < 16 || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(xor4) & 3)) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_read: bytes must be a positive multiple of 16 (got %lld), src 16-byte aligned",
+                 (long long)bytes);
+        return FPTQ_PROBE_ERR_SHAPE;
+    }
     const int64_t n16 = bytes / 16, blocks = (n16 + 256 * 8 - 1) / (256 * 8);
     const unsigned grid = (unsigned)(blocks < PROBE_READ_WORKGROUPS ? blocks : PROBE_READ_WORKGROUPS);
-    probe_read_kernel<<<dim3(grid), dim3(256), 0, s>>>((const v4i *)src, n16, xor4);
-    return hipGetLastError();
+    probe_read_kernel<<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>((const v4i *)src, n16, xor4);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_read: %s", hipGetErrorString(e));
+        return FPTQ_PROBE_ERR_HIP;
+    }
+    return 0;
 }
 
-}  // namespace fptq
+}  // extern "C"

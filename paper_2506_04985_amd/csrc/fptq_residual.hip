@@ -24,10 +24,12 @@ __device__ inline uint32_t r_pack_bf16(float lo, float hi)
 // WPR waves per row: 1 (four rows per workgroup; no LDS, no barrier: for many short rows) or 4 (a workgroup per
 // row).  CH > 0: K % 8 == 0, K <= 512 * WPR * CH, rows 16-byte aligned, z kept in registers.
 // CH == 0 (WPR = 1): any K, the inputs are read twice (the second time from cache).
+// x_next may be the same buffer as xr or yb (the update in place), so none of the three is declared restrict: every
+// thread reads an element of its row before it stores that element, and no thread touches another's elements.
 template <int CH, int WPR>
-__global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint16_t *__restrict__ xr, const uint16_t *__restrict__ yb,
+__global__ __launch_bounds__(256) void residual_norm_quantize_kernel(const uint16_t *xr, const uint16_t *yb,
                                                                      int64_t M, int64_t K, const float *__restrict__ s_prev,
-                                                                     float eps, float inv_s_a, uint16_t *__restrict__ x_next,
+                                                                     float eps, float inv_s_a, uint16_t *x_next,
                                                                      float *__restrict__ s_next, uint8_t *__restrict__ out)
 {
     static_assert(WPR == 1 || (WPR == 4 && CH > 0), "a wave or a workgroup per row");

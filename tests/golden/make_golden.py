@@ -15,7 +15,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
 from oracle import linear as oracle            # noqa: E402
-from paper_2506_04985_amd import synth         # noqa: E402
+import fptq_workloads as synth         # noqa: E402
 
 
 def digests():

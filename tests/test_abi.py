@@ -5,22 +5,27 @@ import os
 import re
 
 from paper_2506_04985_amd import binding as fptq
+from paper_2506_04985_amd import probe
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_symbols():
-    text = open(os.path.join(ROOT, "include", "fptq.h")).read()
+def header_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(fptq_[a-z0-9_]+)\s*\(", text)))
 
 
-def test_library_exports_every_declared_symbol():
-    L = fptq.lib()
-    names = header_symbols()
-    assert set(names) == set(fptq.EXPORTS)
-    for n in names:
-        assert getattr(L, n) is not None
+def test_libraries_export_every_declared_symbol():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["fptq.h", "fptq_probe.h", "fptq_testing.h"]
+    for header, L, exports in (("fptq.h", fptq.lib(), fptq.EXPORTS), ("fptq_testing.h", fptq.lib(), fptq.TESTING_EXPORTS),
+                               ("fptq_probe.h", probe.lib(), probe.EXPORTS)):
+        names = header_symbols(header)
+        assert set(names) == set(exports), header
+        for n in names:
+            assert getattr(L, n) is not None
+    # the measurement aids are not part of the product library
+    assert not hasattr(fptq.lib(), "fptq_probe_read")
 
 
 def test_host_only_entry_points():
@@ -43,6 +48,22 @@ def test_host_only_entry_points():
     assert L.fptq_quantize_act(dummy, 4, 4, 1, 0.0, None, 1.0, dummy, 8, None, None) == -3
     assert L.fptq_w4a4_linear(dummy, dummy, 4, 0, 4, 1.0, dummy, None, dummy, None, None) == -2
     assert L.fptq_w4a4_linear(dummy, dummy, 4, 4, 4, float("inf"), dummy, None, dummy, None, None) == -6
+
+
+def test_k_beyond_exact_int32_accumulation_is_refused():
+    """|q w| <= 64, so INT32 sums are exact up to K = 2^25 - 1; with a zero point the epilogue's acc - z * sum_k w
+    needs K <= 2^24 - 1.  Longer sums are refused before anything is launched."""
+    L = fptq.lib()
+    dummy = ctypes.c_void_p(4096)
+    big, big_zp = (1 << 25) - 1, (1 << 24) - 1
+    for fn in (L.fptq_w4a4_linear, L.fptq_w4a4_linear_ref):
+        assert fn(dummy, dummy, 1, 1, big + 1, 1.0, dummy, None, dummy, None, None) == -2
+        assert b"INT32" in L.fptq_last_error()
+    assert L.fptq_w4a4_linear_ws(dummy, dummy, 1, 1, big + 1, 1.0, dummy, None, dummy, None, None, 0, None) == -2
+    assert L.fptq_w4a4_linear_zp(dummy, dummy, 1, 1, big_zp + 1, 1.0, dummy, None, 3, dummy, dummy, None, None) == -2
+    assert L.fptq_w4a4_linear_zp(dummy, dummy, 1, 1, big + 1, 1.0, dummy, None, 0, None, dummy, None, None) == -2
+    assert L.fptq_linear_workspace_bytes(1, 1, big + 1) == -2
+    assert L.fptq_linear_workspace_bytes(256, 1024, big) >= 0
 
 
 def test_workspace_size_is_host_arithmetic():

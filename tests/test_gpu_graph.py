@@ -48,7 +48,7 @@ def test_replays_match_eager_results():
         return {k: t[k].clone() for k in outputs}
 
     fresh_inputs(0)
-    run_block(t)                                   # eager once: every kernel has run before anything is captured
+    fptq.fptq_init()                               # the device is set up; no kernel of the block has to run before the capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()

@@ -11,7 +11,7 @@ import pytest
 import torch
 
 from paper_2506_04985_amd import binding as fptq
-from paper_2506_04985_amd import synth
+import fptq_workloads as synth
 
 from gpu_util import Y_TOL, dev, dev_bf16, host_bits, layout_from_canonical, run_gpu_linear, y_error
 

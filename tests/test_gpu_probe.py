@@ -3,22 +3,22 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2506_04985_amd import binding as fptq
+from paper_2506_04985_amd import probe
 
 pytestmark = pytest.mark.gpu
 
 
 def test_mfma_probe_counts_and_is_deterministic():
-    ops, out0 = fptq.fptq_probe_mfma_rate(3, 0)
+    ops, out0 = probe.mfma_rate(3, 0)
     assert ops == 256 * 4 * 3 * 64 * 65536
     assert int(out0.abs().max()) == 0                       # zero operands: zero accumulators
-    _, a = fptq.fptq_probe_mfma_rate(5, 1)
-    _, b = fptq.fptq_probe_mfma_rate(5, 1)
+    _, a = probe.mfma_rate(5, 1)
+    _, b = probe.mfma_rate(5, 1)
     torch.cuda.synchronize()
     assert torch.equal(a, b) and int((a != 0).sum()) > 60000
     for bad in (0, -1, (1 << 20) + 1):
-        with pytest.raises(fptq.FptqError) as e:
-            fptq.fptq_probe_mfma_rate(bad, 1)
+        with pytest.raises(probe.ProbeError) as e:
+            probe.mfma_rate(bad, 1)
         assert e.value.code == -6
 
 
@@ -26,12 +26,12 @@ def test_mfma_probe_counts_and_is_deterministic():
 def test_read_probe_sees_every_word(nbytes):
     rng = np.random.default_rng(nbytes)
     host = rng.integers(-2**31, 2**31 - 1, nbytes // 4, dtype=np.int64).astype(np.int32)
-    x = fptq.fptq_probe_read(torch.from_numpy(host).cuda()).cpu().numpy()
+    x = probe.read(torch.from_numpy(host).cuda()).cpu().numpy()
     assert np.array_equal(x, np.bitwise_xor.reduce(host.reshape(-1, 4), axis=0))
 
 
 def test_read_probe_rejects_bad_sizes():
     buf = torch.zeros(40, dtype=torch.uint8, device="cuda")
-    with pytest.raises(fptq.FptqError) as e:
-        fptq.fptq_probe_read(buf)                            # 40 is not a multiple of 16
+    with pytest.raises(probe.ProbeError) as e:
+        probe.read(buf)                            # 40 is not a multiple of 16
     assert e.value.code == -2

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from paper_2506_04985_amd import binding as fptq
-from paper_2506_04985_amd import synth
+import fptq_workloads as synth
 
 from gpu_util import dev, dev_bf16, host_bits
 
@@ -47,3 +47,21 @@ def test_residual_step_in_place_and_then_linear(oracle):
     acc_ref = oracle.gemm_i64(ref["q"], w).astype(np.int32)
     assert np.array_equal(acc.cpu().numpy(), acc_ref)
     assert np.array_equal(host_bits(y), oracle.epilogue(acc_ref, np.float32(0.5), s_w))
+
+
+@pytest.mark.parametrize("alias", ["x_res", "y"])
+@pytest.mark.parametrize("M,K", [(5, 129), (130, 1000), (3, 16390), (2, 20000)])
+def test_residual_step_in_place_on_the_two_pass_path(oracle, M, K, alias):
+    """K not a multiple of 8, or above 16384: the kernel that reads its inputs twice.  The output may be either input."""
+    rng = np.random.default_rng(M + K)
+    xb = synth.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32) * 2)
+    yb = synth.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    sp = rng.uniform(0.2, 3, M).astype(np.float32)
+    xd, yd = dev_bf16(xb), dev_bf16(yb)
+    target = xd if alias == "x_res" else yd
+    x_next, s_next, xq = fptq.fptq_residual_norm_quantize(xd, yd, 0.45, dev(sp), 1e-5, x_next=target)
+    ref = oracle.residual_norm_quantize(xb, yb, np.float32(0.45), sp, 1e-5)
+    assert x_next.data_ptr() == target.data_ptr()
+    assert np.array_equal(host_bits(target), ref["x_next"])
+    assert np.array_equal(s_next.cpu().numpy().view(np.uint32), ref["s_next"].view(np.uint32))
+    assert np.array_equal(fptq.fptq_unpack(xq, M, K).cpu().numpy(), ref["q"])

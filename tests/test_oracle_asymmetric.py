@@ -5,7 +5,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from paper_2506_04985_amd import synth
+import fptq_workloads as synth
 
 
 def test_zero_point_zero_is_the_symmetric_quantizer(oracle):

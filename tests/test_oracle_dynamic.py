@@ -4,7 +4,7 @@ from fractions import Fraction
 
 import numpy as np
 
-from paper_2506_04985_amd import synth
+import fptq_workloads as synth
 
 
 def test_scale_is_absmax_over_seven_and_codes_follow_exact_arithmetic(oracle):

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 from oracle import transforms as T
-from paper_2506_04985_amd import synth
+import fptq_workloads as synth
 
 
 def test_matches_the_kronecker_definition_exactly_on_small_integers(oracle):

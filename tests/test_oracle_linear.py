@@ -8,7 +8,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from paper_2506_04985_amd import synth
+import fptq_workloads as synth
 
 
 def test_gemm_matches_numpy_int64(oracle):

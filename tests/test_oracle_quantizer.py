@@ -119,7 +119,7 @@ def test_quantizer_brute_force_all_bf16(oracle, c):
 
 def test_quantizer_explicit_ties_clamp_and_specials(oracle):
     L = oracle.lib()
-    from paper_2506_04985_amd.synth import f32_to_bf16_bits
+    from fptq_workloads import f32_to_bf16_bits
     b = lambda v: int(f32_to_bf16_bits(np.array([v], np.float32))[0])
     q = lambda v, c: L.oracle_quantize_scalar(b(v), float(np.float32(c)))
     # x * 0.5 is exact: ties go to even
@@ -151,7 +151,7 @@ def test_row_multiplier_is_one_division_then_one_multiply(oracle):
 
 # ------------------------------------------------------------------ row scale (Sec. 3.1.3)
 def test_row_scale_closed_forms(oracle):
-    from paper_2506_04985_amd.synth import f32_to_bf16_bits
+    from fptq_workloads import f32_to_bf16_bits
     K = 256
     # constant row x = c -> S = 1/|c|
     for c in (1.0, -2.0, 0.5, 3.0, -1.5, 0.0078125):
@@ -176,7 +176,7 @@ def test_row_scale_closed_forms(oracle):
 
 def test_row_scale_against_exact_sum(oracle):
     """Random rows: within one fp32 ulp of the value computed from an exactly rounded sum."""
-    from paper_2506_04985_amd.synth import f32_to_bf16_bits, bf16_bits_to_f32
+    from fptq_workloads import f32_to_bf16_bits, bf16_bits_to_f32
     rng = np.random.default_rng(3)
     x = rng.standard_normal((64, 1000)).astype(np.float32)
     x[:, 5] *= 40
@@ -212,7 +212,7 @@ def test_pack_unpack_exhaustive(oracle):
 
 def test_quantize_tensor_uses_the_scalar_rule(oracle):
     """The tensor routine equals the brute-forced scalar rule element by element (ragged sizes)."""
-    from paper_2506_04985_amd.synth import f32_to_bf16_bits
+    from fptq_workloads import f32_to_bf16_bits
     rng = np.random.default_rng(9)
     x = f32_to_bf16_bits(rng.standard_normal((7, 34)).astype(np.float32) * 5)
     r = rng.uniform(0.5, 2, 7).astype(np.float32)

@@ -2,7 +2,7 @@
 import numpy as np
 
 from oracle import transforms as T
-from paper_2506_04985_amd import synth
+import fptq_workloads as synth
 
 
 def test_closed_forms(oracle):

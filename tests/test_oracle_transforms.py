@@ -145,7 +145,7 @@ def test_scale_recursion_equals_definition():
     assert rel(Zts[-1] / T.rms(Zts[-1]), Zs[-1] / T.rms(Zs[-1])) < 1e-10
     # the row scale the oracle's hot path computes is this S_1 (gain-free)
     from oracle import linear
-    from paper_2506_04985_amd.synth import f32_to_bf16_bits, bf16_bits_to_f32
+    from fptq_workloads import f32_to_bf16_bits, bf16_bits_to_f32
     xb = f32_to_bf16_bits(X1.astype(np.float32))
     r = linear.row_scale(xb, linear.MODE_RMS, 0.0)
     want = 1.0 / T.rms(bf16_bits_to_f32(xb).astype(np.float64))[:, 0]
