@@ -60,6 +60,7 @@ def main():
         sys.exit(2)
     import torch
     from paper_2506_04985_amd import binding as fptq
+    from paper_2506_04985_amd import probe
     import fptq_workloads as synth
 
     if not torch.cuda.is_available():
@@ -195,7 +196,7 @@ def main():
            "roofline": roofline}
 
     # ------------------------------------------------------------------ what the device sustains with nothing else going on
-    out["attainable"] = attainable_summary(torch, fptq, dev)
+    out["attainable"] = attainable_summary(torch, probe, dev)
 
     # ------------------------------------------------------------------ activation-side kernels and the widened rows
     out["activation_kernels"] = activation_summary(torch, fptq, dev, x_gu, x_dn, r_dn, s_gu, s_dn, gate, down, layers, xq_dn, ys)
@@ -257,27 +258,27 @@ def all_prefill_shapes(torch, fptq, synth, dev, dev_bf16):
     return rows
 
 
-def attainable_summary(torch, fptq, dev):
+def attainable_summary(torch, probe, dev):
     """Rates of the library's MFMA-only loop (zero and random INT4 operands) and of a streaming read, measured in
     this run: the published peaks are the roofline denominators, these say what the board delivers under load."""
     res = {}
     chk = torch.empty(65536, dtype=torch.int32, device=dev)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for name, dense in (("mfma_loop_zero_operands_tops", 0), ("mfma_loop_random_int4_operands_tops", 1)):
-        fptq.fptq_probe_mfma_rate(500, dense, chk)
+        probe.mfma_rate(500, dense, chk)
         torch.cuda.synchronize()
         e0.record()
-        ops, _ = fptq.fptq_probe_mfma_rate(2000, dense, chk)
+        ops, _ = probe.mfma_rate(2000, dense, chk)
         e1.record()
         torch.cuda.synchronize()
         res[name] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
     x4 = torch.zeros(4, dtype=torch.int32, device=dev)
-    fptq.fptq_probe_read(src, x4)
+    probe.read(src, x4)
     torch.cuda.synchronize()
     e0.record()
     for _ in range(5):
-        fptq.fptq_probe_read(src, x4)
+        probe.read(src, x4)
     e1.record()
     torch.cuda.synchronize()
     res["stream_read_1GiB_GBps"] = round(5 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
