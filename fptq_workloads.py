@@ -48,11 +48,21 @@ class LinearCase:
 
 
 def f32_to_bf16_bits(a):
-    """Round float32 to bf16 (nearest even) and return the bit patterns as uint16."""
-    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    r = u + np.uint32(0x7FFF) + lsb
-    return (r >> np.uint32(16)).astype(np.uint16)
+    """Round float32 to bf16 (nearest even) and return the bit patterns as uint16.  Worked through in blocks of a
+    million values so that the temporaries stay in cache (the big configurations convert hundreds of millions)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).reshape(-1)
+    out = np.empty(u.shape[0], np.uint16)
+    step = 1 << 20
+    for i in range(0, u.shape[0], step):
+        c = u[i:i + step]
+        r = c >> np.uint32(16)
+        r &= np.uint32(1)            # the bit that decides a tie
+        r += np.uint32(0x7FFF)
+        r += c
+        r >>= np.uint32(16)
+        out[i:i + step] = r
+    return out.reshape(a.shape)
 
 
 def bf16_bits_to_f32(b):

@@ -183,7 +183,8 @@ int fptq_w4a4_linear_zp(const void *xq_packed, const void *w_packed, int64_t M, 
  * last one to arrive adds them (integers: the result does not depend on the order) and writes y.
  *   workspace        device, 256-byte aligned, at least fptq_linear_workspace_bytes(M, N, K) bytes, or NULL.
  *                    It must be zero-filled once before its first use; every call leaves the part that has
- *                    to be zero as it found it.  Calls that share a workspace must not overlap in time.
+ *                    to be zero as it found it, so one workspace (sized for the largest problem) can serve calls
+ *                    of any shapes in turn.  Calls that share a workspace must not overlap in time.
  *   workspace_bytes  its size.  Too small, NULL, or a shape that does not profit (fptq_linear_workspace_bytes
  *                    returns 0): the call behaves exactly like fptq_w4a4_linear.
  * Results are identical to fptq_w4a4_linear's.

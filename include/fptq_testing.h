@@ -1,8 +1,11 @@
 /*
- * fptq_testing -- a knob of libfptq.so for its own tests and for tuning runs; applications have no use for it.
+ * fptq_testing -- a knob and a query of libfptq.so for its own tests, profiles and tuning runs; applications have
+ * no use for them.
  */
 #ifndef FPTQ_TESTING_H
 #define FPTQ_TESTING_H
+
+#include <stdint.h>
 
 #ifdef __cplusplus
 extern "C" {
@@ -15,6 +18,14 @@ extern "C" {
  * A forced shape also sends calls with few tokens to the prefill kernel.  Results do not depend on it.
  * Returns 0, or FPTQ_ERR_VALUE (-6) for a value outside 0..8. */
 int fptq_set_gemm_tile(int tile);
+
+/* Host arithmetic only: which kernel fptq_w4a4_linear (with_workspace = 0) or fptq_w4a4_linear_ws with a large enough
+ * workspace (1) would launch for this shape on the current device (an MI355X's 256 compute units are assumed when no
+ * device answers).  kernel receives the tile configuration as it appears in a profiler's kernel name, e.g.
+ * "GemmCfg<2, 2, 4, 4, 4, 1, 1, false>", or "linear_decode_kernel" / "linear_ref_kernel" (workgroups and threads are
+ * 0 for those two); workgroups x threads is the grid a kernel trace shows.  Returns 0 or a negative FPTQ_ERR_* code. */
+int fptq_linear_launch_plan(int64_t M, int64_t N, int64_t K, int with_workspace, char *kernel, int kernel_len,
+                            int64_t *workgroups, int *threads);
 
 #ifdef __cplusplus
 }

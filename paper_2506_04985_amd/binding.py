@@ -20,7 +20,7 @@ EXPORTS = ["fptq_version", "fptq_last_error", "fptq_init", "fptq_packed_bytes", 
            "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic", "fptq_quantize_act_asym",
            "fptq_weight_row_sums", "fptq_w4a4_linear_zp", "fptq_residual_norm_quantize",
            "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_linear_workspace_bytes", "fptq_w4a4_linear_ws"]
-TESTING_EXPORTS = ["fptq_set_gemm_tile"]
+TESTING_EXPORTS = ["fptq_set_gemm_tile", "fptq_linear_launch_plan"]
 
 _lib = None
 
@@ -64,6 +64,8 @@ def lib():
         for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p]
+        L.fptq_linear_launch_plan.restype = i32
+        L.fptq_linear_launch_plan.argtypes = [i64, i64, i64, i32, ctypes.c_char_p, i32, ctypes.POINTER(i64), ctypes.POINTER(i32)]
         L.fptq_set_gemm_tile.restype = i32
         L.fptq_set_gemm_tile.argtypes = [i32]
         L.fptq_unpack.restype = i32
@@ -255,6 +257,14 @@ def fptq_w4a4_linear_ref(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None
 
 def fptq_set_gemm_tile(tile):
     _check(lib().fptq_set_gemm_tile(int(tile)))
+
+
+def fptq_linear_launch_plan(M, N, K, with_workspace=False):
+    """(kernel name fragment, workgroups, threads per workgroup) of the launch a linear call would make; host only."""
+    buf = ctypes.create_string_buffer(96)
+    wgs, thr = ctypes.c_int64(0), ctypes.c_int(0)
+    _check(lib().fptq_linear_launch_plan(M, N, K, int(bool(with_workspace)), buf, len(buf), ctypes.byref(wgs), ctypes.byref(thr)))
+    return buf.value.decode(), int(wgs.value), int(thr.value)
 
 
 def fptq_unpack(packed, rows, K):

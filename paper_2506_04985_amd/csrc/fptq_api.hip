@@ -365,6 +365,31 @@ int fptq_w4a4_linear_ws(const void *xq_packed, const void *w_packed, int64_t M, 
                          acc_dbg, stream, workspace, workspace_bytes);
 }
 
+int fptq_linear_launch_plan(int64_t M, int64_t N, int64_t K, int with_workspace, char *kernel, int kernel_len,
+                            int64_t *workgroups, int *threads)
+{
+    const char *fn = "fptq_linear_launch_plan";
+    if (!kernel || kernel_len < 1 || !workgroups || !threads) {
+        set_error("%s: NULL pointer", fn);
+        return FPTQ_ERR_NULL;
+    }
+    int rc;
+    if ((rc = check_dims(fn, M, K, "M", "K")) || (rc = check_dims(fn, N, K, "N", "K")) || (rc = check_dims(fn, M, N, "M", "N")))
+        return rc;
+    LinearPlan plan = {};
+    if (few_token_shape(M, N) && forced_gemm_tile() == 0) {
+        snprintf(plan.kernel, sizeof plan.kernel, "linear_decode_kernel");
+        plan.workgroups = 0;
+        plan.threads = 0;
+    } else {
+        linear_mfma_plan(M, N, K, with_workspace != 0, &plan);
+    }
+    snprintf(kernel, (size_t)kernel_len, "%s", plan.kernel);
+    *workgroups = plan.workgroups;
+    *threads = plan.threads;
+    return FPTQ_OK;
+}
+
 int fptq_set_gemm_tile(int tile)
 {
     if (tile < 0 || tile > 8) {

@@ -51,6 +51,14 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
 void set_gemm_tile(int tile);
 int forced_gemm_tile();
 
+// What a linear call would launch: kernel (template instance or name), workgroups, threads per workgroup.
+struct LinearPlan {
+    char kernel[96];
+    int64_t workgroups;
+    int threads;
+};
+void linear_mfma_plan(int64_t M, int64_t N, int64_t K, bool with_workspace, LinearPlan *plan);
+
 // Per-device state, set up once per device (by fptq_init or by the first call that needs it; thread-safe):
 // the number of compute units, which the launchers size their grids and pick their tile shapes by.
 constexpr int MAX_DEVICES = 64;

@@ -15,6 +15,7 @@
 // -> widen -> MFMA.  The 16-byte granules of a row are XOR-swizzled in LDS so that the fragment
 // reads are bank-conflict free.
 #include <cmath>
+#include <cstdio>
 
 #include "fptq_common.h"
 
@@ -33,6 +34,7 @@ constexpr int WAIT_LGKM0 = 15 | (3 << 14) | (7 << 4) | (0 << 8);
 constexpr int RSRC_FLAGS = 0x00020000;
 
 constexpr int MAX_SPLITS = 4;     // K ranges per output tile in the split-K variant
+constexpr int SPLIT_COUNTERS = 1024;   // arrival counters at the start of a split-K workspace (one per output tile)
 
 // OCC_ = workgroups meant to share a CU (caps the register budget: 512 / OCC_ per lane).  KS_ = K groups:
 // KS_ sets of WAVES waves work on the same output tile, set g on K tiles g, g + KS_, ..., each with its own
@@ -128,12 +130,13 @@ __device__ inline void finish(v16i (&a)[TNE][TME], const float (&scv)[(TNE * 32 
     // a device-wide fence would write back and invalidate a whole L2 per workgroup; instead the partials are
     // stored and loaded with the device-coherent cache policy (sc0 sc1: written through to, and read from, the
     // memory side), the stores are complete (vmcnt) before the arrival is counted, and the count is an atomic
-    // at the same scope.  Workspace: [total] arrival counters (zero between calls), then
+    // at the same scope.  Workspace: SPLIT_COUNTERS arrival counters (zero between calls; the first `total` are used:
+    // a region of fixed size, so that calls of different shapes that share a workspace agree on where it ends), then
     // [splits][total][sub-tile][quad][threads of a K group] partials as 16-byte quads, lane-contiguous.
     if (C::SPLIT) {
         constexpr int TPG = C::WAVES * 64, COHERENT = 1 | 16;     // aux bits: sc0, sc1
         const int64_t slice = (int64_t)C::ACC_REGS * TPG;
-        int32_t *counters = ws, *parts = ws + ((total + 63) & ~63);
+        int32_t *counters = ws, *parts = ws + SPLIT_COUNTERS;
         int *flag = reinterpret_cast<int *>(lds + C::LDS_BYTES - 16);     // clear of the epilogue's patches
         const int qoff = (wave * 64 + lane) * 16 + sub0 * (4 * TPG * 16);
         const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
@@ -630,7 +633,7 @@ static int64_t split_tiles(int64_t M, int64_t N) { return ((N + T64x64k4split::B
 static int split_count(int64_t M, int64_t N, int64_t K, int cus)
 {
     const int64_t tiles = split_tiles(M, N), kt = k_tiles(K);
-    if (tiles > cus / 2 || K > 131071 || kt < 48) return 1;
+    if (tiles > cus / 2 || tiles > SPLIT_COUNTERS || K > 131071 || kt < 48) return 1;
     int64_t sp = cus / tiles;
     if (sp > kt / 16) sp = kt / 16;
     if (sp > MAX_SPLITS) sp = MAX_SPLITS;
@@ -644,7 +647,7 @@ int64_t linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
     const int sp = split_count(M, N, K, device_cus_or_default());
     if (sp < 2) return 0;
     const int64_t tiles = split_tiles(M, N);
-    return (((tiles + 63) & ~(int64_t)63) + sp * tiles * T64x64k4split::ACC_REGS * (T64x64k4split::WAVES * 64)) * 4;
+    return (SPLIT_COUNTERS + sp * tiles * T64x64k4split::ACC_REGS * (T64x64k4split::WAVES * 64)) * 4;
 }
 
 hipError_t launch_linear_mfma_ws(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
@@ -657,14 +660,12 @@ hipError_t launch_linear_mfma_ws(const uint8_t *xq, const uint8_t *wq, int64_t M
     return launch_cfg<T64x64k4split>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, sp);
 }
 
-hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
-                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
-                              hipStream_t s)
+// Tile shape for a problem: index into the launch table (0 = 256 x 256, 1 = 192 x 256, 2 = 256 x 128, 3 = 256 x 128 with
+// two workgroups per CU, 4 = 128 x 128 and 5 = 256 x 128 with two K groups, 6 = 64 x 64 and 7 = 128 x 64 with four).
+static int choose_tile(int64_t M, int64_t N, int64_t K, int cus)
 {
-    // Limits of this kernel: the widened accumulator is 256 * acc with |acc| <= 64 K, and one K tile
-    // of all rows (rows * 64 bytes) must fit a 32-bit buffer descriptor.  Beyond them the simple
-    // kernel answers.
-    if (K > 131071 || (wsum && K > 65535) || M > (1 << 24) || N > (1 << 24)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    const int forced = forced_gemm_tile();
+    if (forced > 0) return forced - 1;
     // Estimated time in microseconds, fitted to measurements on uniform random operands on MI355X (the clock is
     // power-limited there, so a K tile costs about the same time whatever the MFMA utilisation):
     // one-workgroup-per-CU shapes run ceil(tiles / CUs) rounds of (fixed + per-K-tile) each.  With two
@@ -674,7 +675,7 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     // measured at r = 0.6).  At most one 256 x 128 tile per CU: the two-K-group variant, whose K tiles go
     // faster the fewer CUs are busy (0.67 us at 256 tiles, 0.55 at 160: the power limit again).
     auto tiles = [&](int64_t bn, int64_t bm) { return (double)(((N + bn - 1) / bn) * ((M + bm - 1) / bm)); };
-    const double kt = (double)k_tiles(K), CUS = (double)device_cus_or_default();
+    const double kt = (double)k_tiles(K), CUS = (double)cus;
     const double t21 = tiles(256, 128), x = t21 / (2 * CUS), frac = x - floor(x);
     const double rounds_o2 = x < 1.0 ? 0.7 + 0.3 * x : floor(x) + (frac > 0 ? fmax(frac, 0.5 + 0.15 * frac) : 0.0);
     const double never = 1e30;
@@ -685,31 +686,78 @@ hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, i
         t21 > CUS ? rounds_o2 * (7.8 + 1.304 * kt) : never,
         t21 <= CUS ? 8.5 + (0.35 + 0.32 * t21 / CUS) * kt : never,
     };
-    const int forced = forced_gemm_tile();
-    int pick = forced > 0 ? forced - 1 : 0;
-    if (forced <= 0) {
-        for (int i = 1; i < 5; ++i)
-            if (cost[i] < cost[pick]) pick = i;
-        if (pick == 4) pick = 5;       // the launch table below: 4 = 128 x 128, 5 = 256 x 128, both with two K groups
-        // Problems so small that even 128 x 128 tiles give every CU at most one workgroup take that tile: the
-        // kernel time is then one workgroup's walk through K and the small tile walks fastest (17 against 25 us at
-        // K = 4096).  A deeper ring does not help there.
-        if (tiles(128, 128) <= CUS) pick = 4;
-        // Fewer tiles still: the smallest tile shape that still gives every CU at most one workgroup, as four K
-        // groups whose waves each hold a whole 64 x 64 block of outputs (half the LDS reads per MFMA of a 32 x 32
-        // block).  Measured at K = 4096, N = 4096: 256 tokens 9 us on 64 x 64 tiles against 17 on 128 x 128; 512
-        // tokens 12.5 us on 128 x 64 against 18.
-        if (tiles(128, 64) <= CUS) pick = 7;
-        if (tiles(64, 64) <= CUS) pick = 6;
+    int pick = 0;
+    for (int i = 1; i < 5; ++i)
+        if (cost[i] < cost[pick]) pick = i;
+    if (pick == 4) pick = 5;       // the launch table: 4 = 128 x 128, 5 = 256 x 128, both with two K groups
+    // Problems so small that even 128 x 128 tiles give every CU at most one workgroup take that tile: the
+    // kernel time is then one workgroup's walk through K and the small tile walks fastest (17 against 25 us at
+    // K = 4096).  A deeper ring does not help there.
+    if (tiles(128, 128) <= CUS) pick = 4;
+    // Fewer tiles still: the smallest tile shape that still gives every CU at most one workgroup, as four K
+    // groups whose waves each hold a whole 64 x 64 block of outputs (half the LDS reads per MFMA of a 32 x 32
+    // block).  Measured at K = 4096, N = 4096: 256 tokens 9 us on 64 x 64 tiles against 17 on 128 x 128; 512
+    // tokens 12.5 us on 128 x 64 against 18.
+    if (tiles(128, 64) <= CUS) pick = 7;
+    if (tiles(64, 64) <= CUS) pick = 6;
+    return pick;
+}
+
+// Limits of the MFMA kernel: the widened accumulator is 256 * acc with |acc| <= 64 K, and one K tile of all rows
+// (rows * 64 bytes) must fit a 32-bit buffer descriptor.  Beyond them the simple kernel answers.
+static bool mfma_serves(int64_t M, int64_t N, int64_t K, bool zero_point)
+{
+    return !(K > 131071 || (zero_point && K > 65535) || M > (1 << 24) || N > (1 << 24));
+}
+
+template <class C>
+static void describe(int64_t M, int64_t N, int splits, LinearPlan *plan)
+{
+    snprintf(plan->kernel, sizeof plan->kernel, "GemmCfg<%d, %d, %d, %d, %d, %d, %d, %s>", C::WAVES_N, C::WAVES_M, C::TN, C::TM,
+             C::STAGES, C::OCC, C::KS, C::SPLIT ? "true" : "false");
+    plan->workgroups = ((M + C::BM - 1) / C::BM) * ((N + C::BN - 1) / C::BN) * splits;
+    plan->threads = C::THREADS;
+}
+
+// What launch_linear_mfma / launch_linear_mfma_ws would launch for a shape on the current device (host arithmetic only).
+void linear_mfma_plan(int64_t M, int64_t N, int64_t K, bool with_workspace, LinearPlan *plan)
+{
+    const int cus = device_cus_or_default();
+    if (!mfma_serves(M, N, K, false)) {
+        snprintf(plan->kernel, sizeof plan->kernel, "linear_ref_kernel");
+        plan->workgroups = 0;
+        plan->threads = 0;
+        return;
     }
-    if (pick == 1) return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 2) return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 3) return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 4) return launch_cfg<T128x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 5) return launch_cfg<T256x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 6) return launch_cfg<T64x64k4>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    if (pick == 7) return launch_cfg<T128x64k4>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
-    return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    const int sp = with_workspace && forced_gemm_tile() == 0 ? split_count(M, N, K, cus) : 1;
+    if (sp >= 2) return describe<T64x64k4split>(M, N, sp, plan);
+    switch (choose_tile(M, N, K, cus)) {
+    case 1: return describe<T192x256>(M, N, 1, plan);
+    case 2: return describe<T256x128>(M, N, 1, plan);
+    case 3: return describe<T256x128o2>(M, N, 1, plan);
+    case 4: return describe<T128x128k2>(M, N, 1, plan);
+    case 5: return describe<T256x128k2>(M, N, 1, plan);
+    case 6: return describe<T64x64k4>(M, N, 1, plan);
+    case 7: return describe<T128x64k4>(M, N, 1, plan);
+    default: return describe<T256x256>(M, N, 1, plan);
+    }
+}
+
+hipError_t launch_linear_mfma(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
+                              const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
+                              hipStream_t s)
+{
+    if (!mfma_serves(M, N, K, wsum != nullptr)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    switch (choose_tile(M, N, K, device_cus_or_default())) {
+    case 1: return launch_cfg<T192x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    case 2: return launch_cfg<T256x128>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    case 3: return launch_cfg<T256x128o2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    case 4: return launch_cfg<T128x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    case 5: return launch_cfg<T256x128k2>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    case 6: return launch_cfg<T64x64k4>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    case 7: return launch_cfg<T128x64k4>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    default: return launch_cfg<T256x256>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    }
 }
 
 }  // namespace fptq

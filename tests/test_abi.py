@@ -69,10 +69,10 @@ def test_k_beyond_exact_int32_accumulation_is_refused():
 def test_workspace_size_is_host_arithmetic():
     L = fptq.lib()
     f = L.fptq_linear_workspace_bytes
-    assert f(256, 1024, 14336) == (64 + 4 * 64 * 64 * 64) * 4       # 64 tiles of 64 x 64, four K ranges of 28 K tiles
-    assert f(129, 128, 12288) == (64 + 4 * 6 * 64 * 64) * 4         # 6 tiles: the counters take a full 64-word line
-    assert f(512, 1024, 12288) == (128 + 2 * 128 * 64 * 64) * 4     # 128 tiles leave room for two ranges
-    assert f(256, 1024, 6144) == (64 + 3 * 64 * 64 * 64) * 4        # 48 K tiles: three ranges of 16
+    assert f(256, 1024, 14336) == (1024 + 4 * 64 * 64 * 64) * 4     # 1024 counters, 64 tiles of 64 x 64, four K ranges of 28 K tiles
+    assert f(129, 128, 12288) == (1024 + 4 * 6 * 64 * 64) * 4       # 6 tiles: the counter region has a fixed size
+    assert f(512, 1024, 12288) == (1024 + 2 * 128 * 64 * 64) * 4    # 128 tiles leave room for two ranges
+    assert f(256, 1024, 6144) == (1024 + 3 * 64 * 64 * 64) * 4      # 48 K tiles: three ranges of 16
     assert f(256, 1024, 4096) == 0 and f(256, 4096, 14336) == 0 and f(64, 1024, 14336) == 0 and f(2048, 11008, 4096) == 0
     assert f(0, 4096, 4096) == -2 and f(256, 4096, -1) == -2
     dummy = ctypes.c_void_p(4096)

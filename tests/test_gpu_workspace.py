@@ -23,8 +23,8 @@ def test_workspace_size_rules():
     assert fptq.fptq_linear_workspace_bytes(256, 1024, 4096) == 0            # K too short to split
     assert fptq.fptq_linear_workspace_bytes(256, 4096, 14336) == 0           # a 64 x 64 tile for every CU already
     n = fptq.fptq_linear_workspace_bytes(256, 1024, 14336)                   # 64 tiles, 4 ranges of 28 K tiles
-    assert n == (64 + 4 * 64 * 64 * 64) * 4
-    assert fptq.fptq_linear_workspace_bytes(256, 2048, 14336) == (128 + 2 * 128 * 64 * 64) * 4
+    assert n == (1024 + 4 * 64 * 64 * 64) * 4
+    assert fptq.fptq_linear_workspace_bytes(256, 2048, 14336) == (1024 + 2 * 128 * 64 * 64) * 4
     with pytest.raises(fptq.FptqError):
         fptq.fptq_linear_workspace_bytes(0, 4096, 4096)
 
@@ -43,7 +43,7 @@ def test_split_matches_oracle(oracle, M, N, K):
         y, acc = fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, float(inp.s_a), dev(inp.s_w), ws, want_acc=True)
         assert np.array_equal(acc.cpu().numpy(), ref["acc"])
         assert np.array_equal(host_bits(y), ref["y"])
-    counters = ws[: 4 * (((N + 63) // 64) * ((M + 63) // 64))]
+    counters = ws[: 4 * 1024]
     assert int(counters.max()) == 0          # arrival counters are back to zero
 
 
@@ -101,3 +101,20 @@ def test_workspace_too_small_or_absent_falls_back():
         y1 = fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, 0.5, s_w, ws)
         assert torch.equal(y0.view(torch.int16), y1.view(torch.int16))
     assert int(small.max()) == 0             # an unusable workspace is not touched
+
+
+def test_calls_of_different_shapes_share_one_workspace():
+    """One workspace, sized for the largest, serves problems of different tile counts in turn: the arrival counters
+    sit in a region of fixed size, so a smaller problem's partial sums never land where a larger one counts."""
+    shapes = [(512, 1024, 14336), (256, 512, 6272), (300, 1000, 12290), (129, 128, 12288), (512, 1024, 14336)]
+    torch.manual_seed(9)
+    ws = torch.zeros(max(fptq.fptq_linear_workspace_bytes(*s) for s in shapes), dtype=torch.uint8, device="cuda")
+    for rep in range(2):
+        for M, N, K in shapes:
+            xq = fptq.fptq_pack_weights(torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda"))
+            wq = fptq.fptq_pack_weights(torch.randint(-8, 8, (N, K), dtype=torch.int8, device="cuda"))
+            s_w = torch.rand(N, device="cuda") * 0.015 + 0.005
+            y0, a0 = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.4, s_w, want_acc=True)
+            y1, a1 = fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, 0.4, s_w, ws, want_acc=True)
+            assert torch.equal(a0, a1) and torch.equal(y0.view(torch.int16), y1.view(torch.int16)), (rep, M, N, K)
+            assert int(ws[: 4 * 1024].max()) == 0
