@@ -194,6 +194,23 @@ int fptq_w4a4_linear_ws(const void *xq_packed, const void *w_packed, int64_t M, 
                         const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *workspace,
                         int64_t workspace_bytes, void *stream);
 
+/*
+ * fptq_w4a4_linear_ws without the workspace argument, for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid it): the split-K exchange goes through a scratch
+ * area built into the library, 4 MiB + 4 KiB of device memory per GPU that the library's code object holds from
+ * load until the process ends.  Nothing is allocated or freed by this call, ever; the per-device set-up (fptq_init,
+ * or the first call on the device) only looks the area's address up.
+ *   - Same arguments, results and errors as fptq_w4a4_linear.  A shape whose split would need more scratch than the
+ *     area holds (possible only on a device with more than 256 compute units) returns FPTQ_ERR_SIZE and launches
+ *     nothing; shapes that would not split K run exactly as in fptq_w4a4_linear.
+ *   - All calls on one GPU share that GPU's area.  Every call leaves the part that must be zero (the arrival
+ *     counters) zero, and writes every partial sum before reading it, so calls in sequence, of any mix of shapes,
+ *     need no clearing in between.  Calls that overlap in time on one GPU (two streams, two threads) race on it
+ *     and must not be made; use fptq_w4a4_linear_ws with one workspace per stream for that.
+ */
+int fptq_w4a4_linear_noalloc(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                             const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream);
+
 /* Same contract as fptq_w4a4_linear but always runs the simple one-thread-per-output kernel
  * (no MFMA, no LDS).  A second, independent GPU implementation used by the tests to cross-check
  * the tuned kernels at full size. */

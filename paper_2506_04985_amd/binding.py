@@ -19,7 +19,8 @@ ERR_NAMES = {-1: "FPTQ_ERR_NULL", -2: "FPTQ_ERR_SHAPE", -3: "FPTQ_ERR_SIZE", -4:
 EXPORTS = ["fptq_version", "fptq_last_error", "fptq_init", "fptq_packed_bytes", "fptq_pack_weights", "fptq_quantize_act",
            "fptq_quantize_act_hadamard", "fptq_quantize_act_dynamic", "fptq_quantize_act_asym",
            "fptq_weight_row_sums", "fptq_w4a4_linear_zp", "fptq_residual_norm_quantize",
-           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_linear_workspace_bytes", "fptq_w4a4_linear_ws"]
+           "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_linear_workspace_bytes", "fptq_w4a4_linear_ws",
+           "fptq_w4a4_linear_noalloc"]
 TESTING_EXPORTS = ["fptq_set_gemm_tile", "fptq_linear_launch_plan"]
 
 _lib = None
@@ -61,7 +62,7 @@ def lib():
         L.fptq_residual_norm_quantize.argtypes = [p, p, i64, i64, p, f32, f32, p, p, p, i64, p]
         L.fptq_quantize_act_dynamic.restype = i32
         L.fptq_quantize_act_dynamic.argtypes = [p, i64, i64, p, i64, p, p]
-        for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref"):
+        for name in ("fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_w4a4_linear_noalloc"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p]
         L.fptq_linear_launch_plan.restype = i32
@@ -249,6 +250,12 @@ def fptq_w4a4_linear_ws(xq, wq, M, N, K, s_a, s_w, workspace, row_out_scale=None
     fn = lambda a, b, m, n, k, sa, sw, d, y, ac, st: lib().fptq_w4a4_linear_ws(
         a, b, m, n, k, sa, sw, d, y, ac, _ptr(workspace), 0 if workspace is None else workspace.numel(), st)
     return _linear(fn, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc)
+
+
+def fptq_w4a4_linear_noalloc(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None, want_acc=False, acc=None):
+    """fptq_w4a4_linear_ws on the library's built-in scratch area.  The library allocates nothing; pass `out` (and `acc`)
+    to keep this wrapper from allocating the result tensors."""
+    return _linear(lib().fptq_w4a4_linear_noalloc, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc)
 
 
 def fptq_w4a4_linear_ref(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None, want_acc=False, acc=None):

@@ -365,6 +365,30 @@ int fptq_w4a4_linear_ws(const void *xq_packed, const void *w_packed, int64_t M, 
                          acc_dbg, stream, workspace, workspace_bytes);
 }
 
+int fptq_w4a4_linear_noalloc(const void *xq_packed, const void *w_packed, int64_t M, int64_t N, int64_t K, float s_a,
+                             const float *s_w, const float *row_out_scale, void *y_bf16, int32_t *acc_dbg, void *stream)
+{
+    const char *fn = "fptq_w4a4_linear_noalloc";
+    // shapes that would not split K anyway need no scratch: the plain layer (which allocates nothing either)
+    const int64_t need = (M >= 1 && N >= 1 && K >= 1 && K <= MAX_K && M <= MAX_ELEMS / K && N <= MAX_ELEMS / K && M <= MAX_ELEMS / N &&
+                          !few_token_shape(M, N))
+                             ? linear_workspace_bytes(M, N, K)
+                             : 0;
+    if (need == 0)
+        return linear_common(fn, nullptr, xq_packed, w_packed, M, N, K, s_a, s_w, row_out_scale, 0, nullptr, y_bf16, acc_dbg, stream);
+    const DeviceInfo *info;
+    hipError_t e = device_info(&info);
+    if (e != hipSuccess) return hip_fail(fn, e);
+    if (need > info->scratch_bytes) {
+        set_error("%s: M=%lld N=%lld K=%lld needs %lld bytes of scratch, the built-in area holds %lld; use fptq_w4a4_linear_ws "
+                  "with a caller workspace or fptq_w4a4_linear", fn, (long long)M, (long long)N, (long long)K, (long long)need,
+                  (long long)info->scratch_bytes);
+        return FPTQ_ERR_SIZE;
+    }
+    return linear_common(fn, nullptr, xq_packed, w_packed, M, N, K, s_a, s_w, row_out_scale, 0, nullptr, y_bf16, acc_dbg, stream,
+                         info->scratch, info->scratch_bytes);
+}
+
 int fptq_linear_launch_plan(int64_t M, int64_t N, int64_t K, int with_workspace, char *kernel, int kernel_len,
                             int64_t *workgroups, int *threads)
 {

@@ -60,12 +60,15 @@ struct LinearPlan {
 void linear_mfma_plan(int64_t M, int64_t N, int64_t K, bool with_workspace, LinearPlan *plan);
 
 // Per-device state, set up once per device (by fptq_init or by the first call that needs it; thread-safe):
-// the number of compute units, which the launchers size their grids and pick their tile shapes by.
+// the number of compute units, which the launchers size their grids and pick their tile shapes by, and the
+// device address of the library's built-in scratch area (fptq_w4a4_linear_noalloc).
 constexpr int MAX_DEVICES = 64;
 constexpr int DEFAULT_CUS = 256;                 // MI355X; used by the host-only size queries when no device answers
 struct DeviceInfo {
     int device;
     int cus;
+    int32_t *scratch;
+    int64_t scratch_bytes;
 };
 hipError_t device_info(const DeviceInfo **out);  // state of the current device
 int device_cus_or_default();                     // compute units of the current device, DEFAULT_CUS without one

@@ -596,6 +596,16 @@ typedef GemmCfg<2, 1, 2, 2, 3, 1, 4> T128x64k4;    // 64 x 64 with one wave per 
 // split K over workgroups, for problems whose 64 x 64 tiles cover at most half of the CUs
 typedef GemmCfg<1, 1, 2, 2, 4, 1, 4, true> T64x64k4split;
 
+// ---- the library's own scratch area, for callers that cannot allocate a workspace: device memory that lives as
+// long as the process, one copy per GPU.  Its name is a host-side handle only; the device address is looked up once
+// per device (gemm_device_init) and that pointer is what kernels and every other host-side use get.  Sized for the
+// split-K exchange on a device of up to 256 CUs: one 64 x 64 INT32 partial tile per workgroup, at most one workgroup
+// per CU, plus the counters.  The arrival counters at its start are zero when the code object is loaded and every
+// launch leaves them zero (the last workgroup of a tile clears its counter); the partial tiles behind them are
+// always written before they are read, so calls in sequence need nothing cleared in between.
+constexpr int64_t SCRATCH_BYTES = (int64_t)256 * T64x64k4split::ACC_REGS * 64 * 4 + 4096;
+static __device__ __align__(256) int32_t scratch[SCRATCH_BYTES / 4];
+
 template <class C, bool ALIGNED, bool DUMP>
 static hipError_t set_lds_attribute()
 {
@@ -616,13 +626,18 @@ static hipError_t set_lds_attributes()
 }
 
 // Once per device, with that device current: every kernel instantiation gets its dynamic-LDS limit (so no launch
-// has to set it later, e.g. under graph capture).
+// has to set it later, e.g. under graph capture), and the scratch area's address on this device is looked up.
 hipError_t gemm_device_init(DeviceInfo *info)
 {
     hipError_t e = set_lds_attributes<T256x256, T192x256, T256x128, T256x128o2, T128x128k2, T256x128k2, T64x64k4, T128x64k4,
                                       T64x64k4split>();
-    (void)info;
-    return e;
+    if (e != hipSuccess) return e;
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    info->scratch = static_cast<int32_t *>(ptr);
+    info->scratch_bytes = SCRATCH_BYTES;
+    return hipSuccess;
 }
 
 // Number of K ranges: as many as keep the workgroup count within the CUs, at most MAX_SPLITS, at least 16 K tiles
