@@ -36,6 +36,15 @@ int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream);
  */
 int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream);
 
+/*
+ * The same read as one burst, the launch pattern of a kernel that is one memory round trip long: `threads` threads per
+ * workgroup (256 or 1024), each issuing `loads` (1, 2, 4 or 8) streaming 16-byte loads at once; the grid covers the
+ * buffer exactly once.  For buffers of a few megabytes this is the read a few-token linear layer cannot beat.
+ *   xor1024  device, 1024 int32 (256 slots of 4), zeroed by the caller: workgroup b XORs into slot b % 256, so that the
+ *            atomics do not serialise on one address; the XOR of all slots is the XOR of the buffer's 16-byte words.
+ */
+int fptq_probe_read_burst(const void *src, int64_t bytes, int32_t *xor1024, int threads, int loads, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,11 @@ extern "C" {
  * Returns 0, or FPTQ_ERR_VALUE (-6) for a value outside 0..8. */
 int fptq_set_gemm_tile(int tile);
 
+/* The same for the few-token kernel's launch shape: 0 = chosen per problem (default), otherwise
+ * waves per workgroup (8 or 16) * 100 + K tiles per batch of loads (1, 2 or 4) * 10 + 16-channel groups per workgroup
+ * (1, 2 or 4), e.g. 1612.  Results do not depend on it.  Returns 0, or FPTQ_ERR_VALUE (-6) for any other value. */
+int fptq_set_decode_shape(int code);
+
 /* Host arithmetic only: which kernel fptq_w4a4_linear (with_workspace = 0) or fptq_w4a4_linear_ws with a large enough
  * workspace (1) would launch for this shape on the current device (an MI355X's 256 compute units are assumed when no
  * device answers).  kernel receives the tile configuration as it appears in a profiler's kernel name, e.g.

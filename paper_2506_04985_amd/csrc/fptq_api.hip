@@ -414,6 +414,15 @@ int fptq_linear_launch_plan(int64_t M, int64_t N, int64_t K, int with_workspace,
     return FPTQ_OK;
 }
 
+int fptq_set_decode_shape(int code)
+{
+    if (!set_decode_shape(code)) {
+        set_error("fptq_set_decode_shape: code must be 0 or waves (8, 16) * 100 + tiles per batch (1, 2, 4) * 10 + channel groups (1, 2, 4)");
+        return FPTQ_ERR_VALUE;
+    }
+    return FPTQ_OK;
+}
+
 int fptq_set_gemm_tile(int tile)
 {
     if (tile < 0 || tile > 8) {

@@ -50,6 +50,7 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
 
 void set_gemm_tile(int tile);
 int forced_gemm_tile();
+bool set_decode_shape(int code);
 
 // What a linear call would launch: kernel (template instance or name), workgroups, threads per workgroup.
 struct LinearPlan {

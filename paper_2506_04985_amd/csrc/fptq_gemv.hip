@@ -158,26 +158,63 @@ static hipError_t launch_decode_cfg(const uint8_t *xq, const uint8_t *wq, int64_
     return hipGetLastError();
 }
 
+// 0 = launch shape chosen per problem; otherwise WAVES * 100 + U * 10 + RT forces one (testing and tuning)
+static std::atomic<int> g_forced_decode{0};
+bool set_decode_shape(int code)
+{
+    const int w = code / 100, u = (code / 10) % 10, rt = code % 10;
+    if (code != 0 && !((w == 8 || w == 16) && (u == 1 || u == 2 || u == 4) && (rt == 1 || rt == 2 || rt == 4))) return false;
+    g_forced_decode.store(code, std::memory_order_relaxed);
+    return true;
+}
+
 hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                                 const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
-                                    hipStream_t s)
+                                hipStream_t s)
 {
     // Limits: M <= 64; 256 * acc must stay in int32; the grid is one workgroup per 16 RT channels.
     if (M > 64 || K > 131071 || N > (1 << 30)) return launch_linear_ref(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s);
+    const int64_t kt = k_tiles(K);
+#define FPTQ_DEC(W, U, MT, RT) return launch_decode_cfg<W, U, MT, RT>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
+    if (const int code = g_forced_decode.load(std::memory_order_relaxed)) {
+        const int mt = M <= 16 ? 1 : M <= 32 ? 2 : 4;
+#define FPTQ_DEC_RT(W, U, MT)                                   \
+    switch (code % 10) {                                        \
+    case 1: FPTQ_DEC(W, U, MT, 1);                              \
+    case 2: FPTQ_DEC(W, U, MT, 2);                              \
+    default:                                                    \
+        if (W * MT <= 32) FPTQ_DEC(W, U, (W * MT <= 32 ? MT : 1), 4); \
+        FPTQ_DEC(W, U, MT, 2);                                  \
+    }
+#define FPTQ_DEC_U(W, MT)                                       \
+    switch ((code / 10) % 10) {                                 \
+    case 1: FPTQ_DEC_RT(W, 1, MT)                               \
+    case 2: FPTQ_DEC_RT(W, 2, MT)                               \
+    default: FPTQ_DEC_RT(W, 4, MT)                              \
+    }
+#define FPTQ_DEC_W(MT)                                          \
+    if (code / 100 == 8) { FPTQ_DEC_U(8, MT) } else { FPTQ_DEC_U(16, MT) }
+        if (mt == 1) { FPTQ_DEC_W(1) }
+        if (mt == 2) { FPTQ_DEC_W(2) }
+        FPTQ_DEC_W(4)
+#undef FPTQ_DEC_W
+#undef FPTQ_DEC_U
+#undef FPTQ_DEC_RT
+    }
     // Shapes chosen by measurement (graph replay over cold weights) on the linear layers of Llama-2-7B/13B,
     // Llama-3-8B/70B and Qwen2-7B: 45 matrices times 1, 16 and 32 tokens, 14 shapes each.  16 waves split K
     // whenever there is at least one K tile per wave: small-N matrices then still put enough loads in flight
     // on every CU, and with the weights on streaming loads one K tile in flight per wave and more resident
     // workgroups beat deeper unrolling (except for very long K against few channels).  Up to 4096 channels a
-    // workgroup takes 16 of them, beyond that 32, which halves the activation re-reads; with more than 16
-    // tokens, 64 from 10240 channels on.  Each choice is within about 10 % of the best shape of its case.
-    const int64_t kt = k_tiles(K);
+    // workgroup takes 16 of them, beyond that 32, which halves the activation re-reads, and 64 from 16384 channels
+    // on (fewer, longer-lived workgroups: the matrix is several rounds of workgroups long either way); with more
+    // than 16 tokens, 64 from 10240 channels on.  Each choice is within about 10 % of the best shape of its case.
     const bool deep = kt >= 16;          // at least one K tile for each of 16 waves
-#define FPTQ_DEC(W, U, MT, RT) return launch_decode_cfg<W, U, MT, RT>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s)
     if (M <= 16) {
         if (!deep) FPTQ_DEC(8, 4, 1, 1);
         if (N <= 4096 && kt >= 80) FPTQ_DEC(16, 2, 1, 1);
         if (N <= 4096) FPTQ_DEC(16, 1, 1, 1);
+        if (N >= 16384) FPTQ_DEC(16, 1, 1, 4);     // 28672 x 4096: 11.7 us against 12.2 with 32 channels per workgroup
         FPTQ_DEC(16, 1, 1, 2);
     }
     if (M <= 32) {

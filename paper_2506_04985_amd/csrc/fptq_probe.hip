@@ -64,6 +64,7 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int dense, i
 // thread XORing 8 16-byte words per step; one atomic per workgroup and component folds the result into
 // xor4 (few enough not to show in the time), which makes the read observable and checkable.
 constexpr int PROBE_READ_WORKGROUPS = 1024;
+constexpr int PROBE_XOR_SLOTS = 256;      // the burst read folds into 256 x 4 words, which the caller XORs together
 
 __global__ __launch_bounds__(256) void probe_read_kernel(const v4i *__restrict__ p, int64_t n16, int32_t *__restrict__ xor4)
 {
@@ -88,6 +89,44 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const v4i *__restrict__
         const int x = part[0][threadIdx.x] ^ part[1][threadIdx.x] ^ part[2][threadIdx.x] ^ part[3][threadIdx.x];
         if (x != 0) atomicXor(xor4 + threadIdx.x, x);
     }
+}
+
+// Burst read: the launch pattern of a kernel that is one memory round trip long.  Every thread issues LOADS
+// streaming 16-byte loads at once (a wave's load covers 1 KB), the grid covers the buffer exactly once, and one
+// atomic per workgroup and component folds the XOR into xor4.  THREADS and LOADS set how many bytes a CU has in flight.
+template <int THREADS, int LOADS>
+__global__ __launch_bounds__(THREADS) void probe_read_burst_kernel(const v4i *__restrict__ p, int64_t n16, int32_t *__restrict__ xor4)
+{
+    __shared__ int32_t part[THREADS / 64][4];
+    const int64_t base = (int64_t)blockIdx.x * (THREADS * LOADS) + threadIdx.x;
+    v4i v[LOADS];
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) v[u] = (base + u * THREADS < n16) ? __builtin_nontemporal_load(p + base + u * THREADS) : v4i{0, 0, 0, 0};
+    v4i r = {0, 0, 0, 0};
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) r ^= v[u];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        int x = r[c];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off, 64);
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6][c] = x;
+    }
+    __syncthreads();
+    if (threadIdx.x < 4) {
+        int x = 0;
+#pragma unroll
+        for (int w = 0; w < THREADS / 64; ++w) x ^= part[w][threadIdx.x];
+        // one of PROBE_XOR_SLOTS places per workgroup: atomics on one address would serialise and show in the time
+        if (x != 0) atomicXor(xor4 + (blockIdx.x % PROBE_XOR_SLOTS) * 4 + threadIdx.x, x);
+    }
+}
+
+template <int THREADS, int LOADS>
+static void launch_burst(const void *src, int64_t n16, int32_t *xor4, hipStream_t s)
+{
+    const int64_t per = (int64_t)THREADS * LOADS;
+    probe_read_burst_kernel<THREADS, LOADS><<<dim3((unsigned)((n16 + per - 1) / per)), dim3(THREADS), 0, s>>>((const v4i *)src, n16, xor4);
 }
 
 }  // namespace fptq_probe
@@ -135,6 +174,41 @@ int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream)
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         snprintf(g_err, sizeof g_err, "fptq_probe_read: %s", hipGetErrorString(e));
+        return FPTQ_PROBE_ERR_HIP;
+    }
+    return 0;
+}
+
+int fptq_probe_read_burst(const void *src, int64_t bytes, int32_t *xor4, int threads, int loads, void *stream)
+{
+    if (!src || !xor4) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_read_burst: NULL pointer");
+        return FPTQ_PROBE_ERR_NULL;
+    }
+    if (bytes < 16 || bytes % 16 != 0 || bytes > ((int64_t)1 << 40) || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(xor4) & 3)) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_read_burst: bytes must be a positive multiple of 16 (got %lld), src 16-byte aligned",
+                 (long long)bytes);
+        return FPTQ_PROBE_ERR_SHAPE;
+    }
+    const int64_t n16 = bytes / 16;
+    hipStream_t s = (hipStream_t)stream;
+    const int key = threads * 10 + loads;
+    switch (key) {
+    case 2561: launch_burst<256, 1>(src, n16, xor4, s); break;
+    case 2562: launch_burst<256, 2>(src, n16, xor4, s); break;
+    case 2564: launch_burst<256, 4>(src, n16, xor4, s); break;
+    case 2568: launch_burst<256, 8>(src, n16, xor4, s); break;
+    case 10241: launch_burst<1024, 1>(src, n16, xor4, s); break;
+    case 10242: launch_burst<1024, 2>(src, n16, xor4, s); break;
+    case 10244: launch_burst<1024, 4>(src, n16, xor4, s); break;
+    case 10248: launch_burst<1024, 8>(src, n16, xor4, s); break;
+    default:
+        snprintf(g_err, sizeof g_err, "fptq_probe_read_burst: threads must be 256 or 1024 and loads 1, 2, 4 or 8");
+        return FPTQ_PROBE_ERR_VALUE;
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_read_burst: %s", hipGetErrorString(e));
         return FPTQ_PROBE_ERR_HIP;
     }
     return 0;

@@ -8,7 +8,7 @@ import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "csrc", "libfptq_probe.so")
-EXPORTS = ["fptq_probe_last_error", "fptq_probe_mfma_rate", "fptq_probe_read"]
+EXPORTS = ["fptq_probe_last_error", "fptq_probe_mfma_rate", "fptq_probe_read", "fptq_probe_read_burst"]
 
 _lib = None
 
@@ -30,6 +30,8 @@ def lib():
         L.fptq_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         L.fptq_probe_read.restype = ctypes.c_int
         L.fptq_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        L.fptq_probe_read_burst.restype = ctypes.c_int
+        L.fptq_probe_read_burst.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -59,6 +61,19 @@ def read(src, xor4=None, nbytes=None):
     xor4 = torch.zeros(4, dtype=torch.int32, device=src.device) if xor4 is None else xor4
     n = src.numel() * src.element_size() if nbytes is None else int(nbytes)
     rc = lib().fptq_probe_read(ctypes.c_void_p(src.data_ptr()), n, ctypes.c_void_p(xor4.data_ptr()), _stream())
+    if rc != 0:
+        _fail(rc)
+    return xor4
+
+
+def read_burst(src, xor1024, threads=1024, loads=2, nbytes=None):
+    """Stream a device buffer once as a single burst of loads (threads per workgroup x loads per thread in flight).
+    xor1024: 1024 zeroed int32 on the device (256 slots of 4); XOR the slots together for the buffer's checksum."""
+    xor4 = xor1024
+    if not src.is_cuda or not src.is_contiguous():
+        raise TypeError("src must be a contiguous CUDA tensor")
+    n = src.numel() * src.element_size() if nbytes is None else int(nbytes)
+    rc = lib().fptq_probe_read_burst(ctypes.c_void_p(src.data_ptr()), n, ctypes.c_void_p(xor4.data_ptr()), int(threads), int(loads), _stream())
     if rc != 0:
         _fail(rc)
     return xor4

@@ -35,3 +35,16 @@ def test_read_probe_rejects_bad_sizes():
     with pytest.raises(probe.ProbeError) as e:
         probe.read(buf)                            # 40 is not a multiple of 16
     assert e.value.code == -2
+
+
+@pytest.mark.parametrize("threads,loads", [(256, 1), (256, 8), (1024, 2), (1024, 4)])
+@pytest.mark.parametrize("nbytes", [16, 16 * 4097, 16 * 1000003])
+def test_burst_read_sees_every_word(nbytes, threads, loads):
+    rng = np.random.default_rng(nbytes + threads + loads)
+    host = rng.integers(-2**31, 2**31 - 1, nbytes // 4, dtype=np.int64).astype(np.int32)
+    slots = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    probe.read_burst(torch.from_numpy(host).cuda(), slots, threads, loads)
+    got = np.bitwise_xor.reduce(slots.cpu().numpy().reshape(256, 4), axis=0)
+    assert np.array_equal(got, np.bitwise_xor.reduce(host.reshape(-1, 4), axis=0))
+    with pytest.raises(probe.ProbeError):
+        probe.read_burst(torch.from_numpy(host).cuda(), slots, 512, 3)
