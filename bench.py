@@ -46,6 +46,11 @@ def parse():
     ap.add_argument("--no-decode", action="store_true", help="skip the decode summary")
     ap.add_argument("--headline-only", action="store_true",
                     help="only the headline workload (c5): no c2 / c3 regions, no activation-kernel, few-tile or attainable-rate sections")
+    ap.add_argument("--warm-seconds", type=float, default=WARM_SECONDS,
+                    help="untimed stepping before each timed region beyond --warmup (0 for counter passes, where every dispatch is slow)")
+    ap.add_argument("--gemm-map", type=int, default=0, choices=(0, 1),
+                    help="workgroup -> tile mapping of the prefill kernel: 0 = the library's XCD-aware default, 1 = launch order "
+                         "(to measure what the mapping is worth)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one elementwise kernel that reads 1 GiB and writes 1 GiB: under rocprofv3 --pmc "
                          "its FETCH_SIZE / WRITE_SIZE readings give the counter scale for a known byte count")
@@ -84,6 +89,7 @@ def main():
         sys.exit(1)
     fptq.lib()          # fail loudly if the HIP library is missing
     fptq.fptq_init()
+    fptq.fptq_set_gemm_map(args.gemm_map)
     dev = torch.device("cuda:0")
 
     def dev_bf16(bits):
@@ -163,7 +169,7 @@ def main():
             # over hundreds of milliseconds, far more than a handful of steps of a small configuration
             n_warm = 0
             t_w = time.perf_counter()
-            while n_warm < warmup or time.perf_counter() - t_w < WARM_SECONDS:
+            while n_warm < warmup or time.perf_counter() - t_w < args.warm_seconds:
                 step(dense)
                 n_warm += 1
                 if n_warm % 8 == 0:
@@ -231,7 +237,8 @@ def main():
            "pct_int8_mfma_peak": round(own["step_TOPS"] / INT8_MFMA_PEAK_TOPS * 100, 2),
            "value_dense_int4_activations": dense["step_TOPS"],
            "pct_int8_mfma_peak_dense_int4_activations": round(dense["step_TOPS"] / INT8_MFMA_PEAK_TOPS * 100, 2),
-           "warmup_note": "after --warmup steps every region keeps stepping untimed until %.1f s have passed" % WARM_SECONDS,
+           "warmup_note": "after --warmup steps every region keeps stepping untimed until %.1f s have passed" % args.warm_seconds,
+           "gemm_map": args.gemm_map,
            "roofline": roofline}
 
     # ------------------------------------------------------------------ the other prefill configurations, same two regions

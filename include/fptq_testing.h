@@ -19,6 +19,12 @@ extern "C" {
  * Returns 0, or FPTQ_ERR_VALUE (-6) for a value outside 0..8. */
 int fptq_set_gemm_tile(int tile);
 
+/* How the prefill kernel's workgroups map to output tiles: 0 (default) = every XCD (the hardware deals consecutive
+ * workgroups to the 8 XCDs in turn) works through a contiguous run of tiles, in bands of 8 N-tiles, so that the tiles
+ * in flight on an XCD share operand panels in its L2; 1 = tiles in launch order, i.e. dealt round-robin to the XCDs
+ * (for measuring what the mapping is worth).  Results do not depend on it.  Returns 0 or FPTQ_ERR_VALUE (-6). */
+int fptq_set_gemm_map(int mode);
+
 /* The same for the few-token kernel's launch shape: 0 = chosen per problem (default), otherwise
  * waves per workgroup (8 or 16) * 100 + K tiles per batch of loads (1, 2 or 4) * 10 + 16-channel groups per workgroup
  * (1, 2 or 4), e.g. 1612.  Results do not depend on it.  Returns 0, or FPTQ_ERR_VALUE (-6) for any other value. */

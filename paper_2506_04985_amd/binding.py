@@ -21,7 +21,7 @@ EXPORTS = ["fptq_version", "fptq_last_error", "fptq_init", "fptq_packed_bytes", 
            "fptq_weight_row_sums", "fptq_w4a4_linear_zp", "fptq_residual_norm_quantize",
            "fptq_w4a4_linear", "fptq_w4a4_linear_ref", "fptq_unpack", "fptq_linear_workspace_bytes", "fptq_w4a4_linear_ws",
            "fptq_w4a4_linear_noalloc"]
-TESTING_EXPORTS = ["fptq_set_gemm_tile", "fptq_set_decode_shape", "fptq_linear_launch_plan"]
+TESTING_EXPORTS = ["fptq_set_gemm_tile", "fptq_set_gemm_map", "fptq_set_decode_shape", "fptq_linear_launch_plan"]
 
 _lib = None
 
@@ -67,6 +67,8 @@ def lib():
             getattr(L, name).argtypes = [p, p, i64, i64, i64, f32, p, p, p, p, p]
         L.fptq_linear_launch_plan.restype = i32
         L.fptq_linear_launch_plan.argtypes = [i64, i64, i64, i32, ctypes.c_char_p, i32, ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.fptq_set_gemm_map.restype = i32
+        L.fptq_set_gemm_map.argtypes = [i32]
         L.fptq_set_decode_shape.restype = i32
         L.fptq_set_decode_shape.argtypes = [i32]
         L.fptq_set_gemm_tile.restype = i32
@@ -262,6 +264,10 @@ def fptq_w4a4_linear_noalloc(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=
 
 def fptq_w4a4_linear_ref(xq, wq, M, N, K, s_a, s_w, row_out_scale=None, out=None, want_acc=False, acc=None):
     return _linear(lib().fptq_w4a4_linear_ref, xq, wq, M, N, K, s_a, s_w, row_out_scale, out, want_acc, acc)
+
+
+def fptq_set_gemm_map(mode):
+    _check(lib().fptq_set_gemm_map(int(mode)))
 
 
 def fptq_set_decode_shape(code):

@@ -414,6 +414,16 @@ int fptq_linear_launch_plan(int64_t M, int64_t N, int64_t K, int with_workspace,
     return FPTQ_OK;
 }
 
+int fptq_set_gemm_map(int mode)
+{
+    if (mode != 0 && mode != 1) {
+        set_error("fptq_set_gemm_map: mode must be 0 or 1");
+        return FPTQ_ERR_VALUE;
+    }
+    set_gemm_map(mode);
+    return FPTQ_OK;
+}
+
 int fptq_set_decode_shape(int code)
 {
     if (!set_decode_shape(code)) {

@@ -49,6 +49,7 @@ hipError_t launch_linear_decode(const uint8_t *xq, const uint8_t *wq, int64_t M,
                                 hipStream_t s);
 
 void set_gemm_tile(int tile);
+void set_gemm_map(int mode);
 int forced_gemm_tile();
 bool set_decode_shape(int code);
 

@@ -272,7 +272,7 @@ template <class C, bool ALIGNED, bool DUMP>
 __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, int tiles_m,
     int tiles_n, float s_a, const float *__restrict__ s_w, const float *__restrict__ d, int zp,
-    const int32_t *__restrict__ wsum, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out, int32_t *ws, int splits)
+    const int32_t *__restrict__ wsum, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out, int32_t *ws, int splits, int map_mode)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         split = pid / total;
         pid -= split * total;
     }
-    {
+    if (map_mode == 0) {                             // (map_mode 1, a measurement aid: tiles dealt round-robin to the XCDs as they come)
         const int per = (total + 7) / 8, tall = total % 8 == 0 ? 8 : total % 8;
         const int xcd = pid % 8, local = pid / 8;
         pid = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
@@ -550,7 +550,9 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
 
 // 0 = choose the tile shape per problem; 1..8 = force one (testing and tuning)
 static std::atomic<int> g_forced_tile{0};
+static std::atomic<int> g_tile_map{0};
 void set_gemm_tile(int tile) { g_forced_tile.store(tile, std::memory_order_relaxed); }
+void set_gemm_map(int mode) { g_tile_map.store(mode, std::memory_order_relaxed); }
 int forced_gemm_tile() { return g_forced_tile.load(std::memory_order_relaxed); }
 
 template <class C, bool ALIGNED, bool DUMP>
@@ -565,7 +567,7 @@ static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, i
     int64_t tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     if (tiles_m * tiles_n * splits > 0x7fffffff) return hipErrorInvalidValue;
     kern<<<dim3((unsigned)(tiles_m * tiles_n * splits)), dim3(C::THREADS), C::LDS_BYTES, s>>>(
-        xq, wq, (int)M, (int)N, (int)k_tiles(K), (int)tiles_m, (int)tiles_n, s_a, s_w, d, zp, wsum, y, acc, ws, splits);
+        xq, wq, (int)M, (int)N, (int)k_tiles(K), (int)tiles_m, (int)tiles_n, s_a, s_w, d, zp, wsum, y, acc, ws, splits, g_tile_map.load(std::memory_order_relaxed));
     return hipGetLastError();
 }
 

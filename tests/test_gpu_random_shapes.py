@@ -50,3 +50,22 @@ def test_random_shapes_against_the_simple_kernel(seed):
             for _ in range(2):
                 y2 = fptq.fptq_w4a4_linear_ws(xq, wq, M, N, K, s_a, s_w, ws, d)
                 assert torch.equal(y2.view(torch.int16), y_ref.view(torch.int16)), where + " (workspace)"
+
+
+def test_launch_order_tile_mapping_gives_the_same_results():
+    """The measurement aid that maps workgroups to tiles in launch order changes which workgroup computes which tile,
+    nothing else."""
+    rng = np.random.default_rng(77)
+    for M, N, K, tile in [(700, 1500, 512, 4), (1100, 2100, 384, 1), (300, 4000, 256, 3), (513, 777, 1024, 0), (260, 900, 12288, 0)]:
+        xq = fptq.fptq_pack_weights(torch.from_numpy(rng.integers(-8, 8, (M, K), dtype=np.int8)).cuda())
+        wq = fptq.fptq_pack_weights(torch.from_numpy(rng.integers(-8, 8, (N, K), dtype=np.int8)).cuda())
+        s_w = torch.from_numpy(rng.uniform(0.005, 0.02, N).astype(np.float32)).cuda()
+        y_ref, a_ref = fptq.fptq_w4a4_linear_ref(xq, wq, M, N, K, 0.3, s_w, want_acc=True)
+        fptq.fptq_set_gemm_tile(tile)
+        fptq.fptq_set_gemm_map(1)
+        try:
+            y, a = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.3, s_w, want_acc=True)
+        finally:
+            fptq.fptq_set_gemm_map(0)
+            fptq.fptq_set_gemm_tile(0)
+        assert torch.equal(a, a_ref) and torch.equal(y.view(torch.int16), y_ref.view(torch.int16)), (M, N, K, tile)
