@@ -162,6 +162,11 @@ def main():
                 if events is not None:
                     e1.record()
                     events.setdefault(L["name"], []).append((e0, e1))
+            if events is not None:      # a bracket around nothing: what the pair of events itself costs
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                e1.record()
+                events.setdefault("", []).append((e0, e1))
 
         res = {}
         for dense in (False, True):
@@ -181,9 +186,14 @@ def main():
                 step(dense, events)
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) / steps * 1e3
+            # A bracket holds the launch between two event packets; the bracket around nothing measures what the second
+            # packet adds (about 5 us), which is subtracted: what remains is the kernel plus the launch latency any stream of
+            # kernels pays (with it the averages agree with a kernel trace of the same run to about 1 us).  Negligible for the
+            # headline launches, 10 % of the shortest ones.
+            pair_us = float(np.mean([a.elapsed_time(b) * 1e3 for a, b in events[""]]))
             launches = {}
             for L in layers:
-                t_us = [a.elapsed_time(b) * 1e3 for a, b in events[L["name"]]]
+                t_us = [a.elapsed_time(b) * 1e3 - pair_us for a, b in events[L["name"]]]
                 avg = float(np.mean(t_us))
                 launches[L["name"]] = {"avg_us": round(avg, 2), "min_us": round(min(t_us), 2), "n": len(t_us),
                                        "TOPS": round(L["ops"] / avg / 1e6, 1),
@@ -191,7 +201,8 @@ def main():
             gemm_us = sum(v["avg_us"] for v in launches.values())
             res["dense_int4_activations" if dense else "own_activations"] = {
                 "ms_per_step": round(ms, 4), "step_TOPS": round(ops_step / ms / 1e9, 1), "warmup_steps_run": n_warm,
-                "gemm_launches_TOPS": round(ops_step / gemm_us / 1e6, 1), "launches": launches}
+                "gemm_launches_TOPS": round(ops_step / gemm_us / 1e6, 1), "event_pair_overhead_us": round(pair_us, 2),
+                "launches": launches}
         return ops_step, res
 
     def config_entry(layers, ops_step, res):
@@ -220,6 +231,7 @@ def main():
                 "frac": round(low["TOPS"] / INT8_MFMA_PEAK_TOPS, 4),
                 "region": "dense_int4_activations" if low is d_dense else "own_activations (the timed region)",
                 "avg_launch_us": low["avg_us"], "ops_per_launch": dom["ops"],
+                "event_pair_overhead_us": dense["event_pair_overhead_us"] if low is d_dense else own["event_pair_overhead_us"],
                 "own_activations": d_own, "dense_int4_activations": d_dense,
                 "traffic": None if trow is None or stale else round(trow["bytes"]),
                 "traffic_source": "profiles/linear_mfma_traffic.md (FETCH_SIZE and WRITE_SIZE counter passes, scaled by a 1 GiB "
