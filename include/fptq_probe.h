@@ -23,12 +23,22 @@ extern "C" {
 const char *fptq_probe_last_error(void);
 
 /*
- * 256 workgroups of 4 waves, each wave issuing iters x 64 v_mfma_i32_32x32x32_i8 on register operands (dense = 0:
- * all zero; otherwise random nibbles in the high half of every byte, the operand form of the prefill kernel).
+ * 256 workgroups of 4 waves, each wave issuing iters x 64 v_mfma_i32_32x32x32_i8 on register operands: dense = 0 all
+ * zero; 1 random nibbles in the high half of every byte (the operand form of the prefill kernel), the same for the whole
+ * run; 2 the same form redrawn every iteration (3.5 VALU instructions per MFMA beside the matrix pipe, about the prefill
+ * kernel's widening load, and inputs that change like real data: the rate the power limit allows a kernel that feeds
+ * the matrix pipe fresh dense operands, before any memory traffic).
  *   out  device, 65536 int32: receives a checksum per thread.
  * Returns the number of integer operations launched (> 0) or a negative error.  The caller times the launch.
  */
 int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream);
+
+/*
+ * The same loop with the choices spelled out: operands 0 zero, 1 fixed random, 2 redrawn every iteration, 3 the
+ * instruction stream of 2 on operands that stay zero (what the extra VALU instructions cost by themselves);
+ * workgroups_per_cu 1 or 2 (one or two waves per SIMD).  out: device, 65536 x workgroups_per_cu int32.
+ */
+int64_t fptq_probe_mfma_rate_ex(int iters, int operands, int workgroups_per_cu, int32_t *out, void *stream);
 
 /*
  * Streams `bytes` (a multiple of 16; src 16-byte aligned) once and XORs all 16-byte words into xor4 (device,

@@ -29,7 +29,10 @@ __device__ inline uint32_t probe_hash(uint32_t x)
 }
 
 // 64 v_mfma_i32_32x32x32_i8 per iteration and wave on 16 independent accumulators, operands held in
-// registers: all zero, or random nibbles in the high half of every byte (the prefill kernel's 16 * v).
+// registers: all zero (dense = 0), random nibbles in the high half of every byte (the prefill kernel's 16 * v) that
+// stay the same for the whole run (1), or the same form redrawn every iteration by an xorshift step per operand word
+// (2: 3.5 VALU instructions per MFMA, about what the prefill kernel's nibble widening costs, and matrix-pipe inputs
+// that change as they do on real data, which is what the board's power limit responds to).
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int dense, int32_t *__restrict__ out)
 {
     v4i a[4], b[4];
@@ -46,11 +49,58 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int dense, i
     for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[i][q] = 0;
-    for (int it = 0; it < iters; ++it) {
+    uint32_t ra[4][4], rb[4][4];      // raw xorshift states behind the operands (dense >= 2)
+    const uint32_t mask = dense == 3 ? 0u : 0xF0F0F0F0u;      // 3: the same instruction stream on operands that stay zero
 #pragma unroll
-        for (int rep = 0; rep < 4; ++rep)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i >> 2], b[i & 3], acc[i], 0, 0, 0);
+        for (int c = 0; c < 4; ++c) {
+            ra[i][c] = probe_hash(threadIdx.x * 131u + i * 4 + c + blockIdx.x * 7919u) | 1u;
+            rb[i][c] = probe_hash(threadIdx.x * 137u + i * 4 + c + blockIdx.x * 104729u) | 1u;
+        }
+    if (dense < 2) {
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i >> 2], b[i & 3], acc[i], 0, 0, 0);
+        }
+    } else {
+        // Fresh operands: while the 64 MFMAs of an iteration consume one operand set, the next set is drawn into a
+        // second one (one xorshift step and a mask per word: 7 VALU), pinned four VALU instructions behind every MFMA
+        // (the prefill kernel's widening is 3 to 4.5 per MFMA), and the sets swap.
+        v4i a2[4], b2[4];
+        auto draw = [&](v4i (&na)[4], v4i (&nb)[4]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    uint32_t x = ra[i][c], y = rb[i][c];
+                    x ^= x << 13, x ^= x >> 17, x ^= x << 5;
+                    y ^= y << 13, y ^= y >> 17, y ^= y << 5;
+                    ra[i][c] = x, rb[i][c] = y;
+                    na[i][c] = (int)(x & mask);
+                    nb[i][c] = (int)(y & mask);
+                }
+        };
+        auto block = [&](const v4i (&ca)[4], const v4i (&cb)[4], v4i (&na)[4], v4i (&nb)[4]) {
+            draw(na, nb);
+#pragma unroll
+            for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ca[i >> 2], cb[i & 3], acc[i], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 64; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        draw(a, b);
+        for (int it = 0; it < iters; it += 2) {
+            block(a, b, a2, b2);
+            block(a2, b2, a, b);
+        }
     }
     int32_t r = 0;
 #pragma unroll
@@ -147,7 +197,9 @@ int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream)
         snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate: iters must be in [1, 2^20]");
         return FPTQ_PROBE_ERR_VALUE;
     }
-    probe_mfma_kernel<<<dim3(PROBE_MFMA_WORKGROUPS), dim3(256), 0, (hipStream_t)stream>>>(iters, dense != 0, out);
+    dense = dense < 0 ? 0 : dense > 3 ? 3 : dense;
+    if (dense >= 2) iters = (iters + 1) & ~1;            // the fresh-operand loop runs iterations in pairs
+    probe_mfma_kernel<<<dim3(PROBE_MFMA_WORKGROUPS), dim3(256), 0, (hipStream_t)stream>>>(iters, dense, out);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate: %s", hipGetErrorString(e));
@@ -155,6 +207,27 @@ int64_t fptq_probe_mfma_rate(int iters, int dense, int32_t *out, void *stream)
     }
     // workgroups x waves x iterations x MFMAs per iteration x operations of one 32x32x32 MFMA
     return (int64_t)PROBE_MFMA_WORKGROUPS * 4 * iters * 64 * (2 * 32 * 32 * 32);
+}
+
+int64_t fptq_probe_mfma_rate_ex(int iters, int operands, int workgroups_per_cu, int32_t *out, void *stream)
+{
+    if (!out) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate_ex: NULL pointer");
+        return FPTQ_PROBE_ERR_NULL;
+    }
+    if (iters < 1 || iters > (1 << 20) || operands < 0 || operands > 3 || workgroups_per_cu < 1 || workgroups_per_cu > 2) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate_ex: iters in [1, 2^20], operands in 0..3, workgroups_per_cu 1 or 2");
+        return FPTQ_PROBE_ERR_VALUE;
+    }
+    const int wgs = PROBE_MFMA_WORKGROUPS * workgroups_per_cu;
+    if (operands >= 2) iters = (iters + 1) & ~1;         // the fresh-operand loop runs iterations in pairs
+    probe_mfma_kernel<<<dim3(wgs), dim3(256), 0, (hipStream_t)stream>>>(iters, operands, out);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(g_err, sizeof g_err, "fptq_probe_mfma_rate_ex: %s", hipGetErrorString(e));
+        return FPTQ_PROBE_ERR_HIP;
+    }
+    return (int64_t)wgs * 4 * iters * 64 * (2 * 32 * 32 * 32);
 }
 
 int fptq_probe_read(const void *src, int64_t bytes, int32_t *xor4, void *stream)

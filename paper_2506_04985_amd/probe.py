@@ -8,7 +8,7 @@ import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "csrc", "libfptq_probe.so")
-EXPORTS = ["fptq_probe_last_error", "fptq_probe_mfma_rate", "fptq_probe_read", "fptq_probe_read_burst"]
+EXPORTS = ["fptq_probe_last_error", "fptq_probe_mfma_rate", "fptq_probe_read", "fptq_probe_read_burst", "fptq_probe_mfma_rate_ex"]
 
 _lib = None
 
@@ -30,6 +30,8 @@ def lib():
         L.fptq_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         L.fptq_probe_read.restype = ctypes.c_int
         L.fptq_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        L.fptq_probe_mfma_rate_ex.restype = ctypes.c_int64
+        L.fptq_probe_mfma_rate_ex.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         L.fptq_probe_read_burst.restype = ctypes.c_int
         L.fptq_probe_read_burst.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         _lib = L
@@ -47,7 +49,7 @@ def _fail(code):
 def mfma_rate(iters, dense, out=None):
     """Launch the MFMA-only loop; returns (integer operations launched, per-thread checksums).  The caller times it."""
     out = torch.empty(65536, dtype=torch.int32, device="cuda") if out is None else out
-    ops = lib().fptq_probe_mfma_rate(int(iters), int(bool(dense)), ctypes.c_void_p(out.data_ptr()), _stream())
+    ops = lib().fptq_probe_mfma_rate(int(iters), int(dense), ctypes.c_void_p(out.data_ptr()), _stream())
     if ops < 0:
         _fail(ops)
     return int(ops), out
@@ -77,3 +79,12 @@ def read_burst(src, xor1024, threads=1024, loads=2, nbytes=None):
     if rc != 0:
         _fail(rc)
     return xor4
+
+
+def mfma_rate_ex(iters, operands, workgroups_per_cu, out):
+    """The MFMA loop with explicit operand mode (0 zero, 1 fixed, 2 fresh, 3 fresh instruction stream on zeros) and one or
+    two workgroups per CU; out: 65536 x workgroups_per_cu int32 on the device.  Returns the operations launched."""
+    ops = lib().fptq_probe_mfma_rate_ex(int(iters), int(operands), int(workgroups_per_cu), ctypes.c_void_p(out.data_ptr()), _stream())
+    if ops < 0:
+        _fail(ops)
+    return int(ops)

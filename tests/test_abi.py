@@ -4,6 +4,8 @@ import ctypes
 import os
 import re
 
+import pytest
+
 from paper_2506_04985_amd import binding as fptq
 from paper_2506_04985_amd import probe
 
@@ -80,3 +82,27 @@ def test_workspace_size_is_host_arithmetic():
     assert L.fptq_w4a4_linear_ws(dummy, dummy, 256, 4096, 14336, 1.0, dummy, None, dummy, None, odd, 1 << 30, None) == -7
     assert L.fptq_w4a4_linear_ws(dummy, dummy, 256, 4096, 14336, 1.0, dummy, None, dummy, None, dummy, -5, None) == -3
     assert L.fptq_w4a4_linear_ws(None, dummy, 256, 4096, 14336, 1.0, dummy, None, dummy, None, dummy, 0, None) == -1
+
+
+def test_testing_knobs_validate_and_the_launch_plan_is_host_arithmetic():
+    L = fptq.lib()
+    for bad in (-1, 9, 100):
+        assert L.fptq_set_gemm_tile(bad) == -6
+    for bad in (-1, 2):
+        assert L.fptq_set_gemm_map(bad) == -6
+    for bad in (1, 811 + 1000, 1631, 1615, 911):
+        assert L.fptq_set_decode_shape(bad) == -6
+    for ok in (811, 1624, 0):
+        assert L.fptq_set_decode_shape(ok) == 0
+    assert L.fptq_set_gemm_tile(0) == 0 and L.fptq_set_gemm_map(0) == 0
+    # the shapes of the benchmark configurations on a 256-CU device: large tiles, two workgroups per CU or one
+    plan = fptq.fptq_linear_launch_plan
+    assert plan(8192, 57344, 8192) == ("GemmCfg<2, 2, 4, 2, 3, 2, 1, false>", 224 * 64, 256)
+    assert plan(8192, 8192, 28672) == ("GemmCfg<2, 2, 4, 4, 4, 1, 1, false>", 32 * 32, 256)
+    assert plan(2048, 4096, 11008) == ("GemmCfg<2, 2, 4, 2, 3, 1, 2, false>", 16 * 16, 512)
+    assert plan(256, 1024, 8192) == ("GemmCfg<1, 1, 2, 2, 4, 1, 4, false>", 64, 256)
+    assert plan(256, 1024, 8192, True) == ("GemmCfg<1, 1, 2, 2, 4, 1, 4, true>", 64 * 4, 256)
+    assert plan(8, 4096, 4096)[0] == "linear_decode_kernel" and plan(64, 28672, 4096)[0].startswith("GemmCfg")
+    assert plan(300, 300, 200000)[0] == "linear_ref_kernel"
+    with pytest.raises(fptq.FptqError):
+        plan(0, 4, 4)

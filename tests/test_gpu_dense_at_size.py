@@ -121,3 +121,20 @@ def test_one_k_tile_at_a_time(oracle, name, M, N, K, stride):
         acc_ref = oracle.gemm_i32(np.ascontiguousarray(x[:, k0:k1]), np.ascontiguousarray(w[:, k0:k1]))
         assert torch.equal(acc, torch.from_numpy(acc_ref).cuda()), (name, j)
     assert np.array_equal(host_bits(y), oracle.epilogue(acc_ref, np.float32(0.5), s_w)), name
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 1024, 8192), (256, 2048, 12288), (512, 1024, 14336), (200, 1000, 28672)])
+def test_dense_split_k_whole_tensor(oracle, M, N, K):
+    """The workspace path (K split over several workgroups per 64 x 64 tile) and the same through the library's built-in
+    scratch area, on dense operands against the oracle."""
+    x, w, s_w, d = dense_inputs(M, N, K, 5)
+    nbytes = fptq.fptq_linear_workspace_bytes(M, N, K)
+    assert nbytes > 0
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    acc_ref = oracle.gemm_i32(x, w)
+    y_ref = oracle.epilogue(acc_ref, np.float32(0.29), s_w, d)
+    for entry in (lambda *a, **k: fptq.fptq_w4a4_linear_ws(*a[:7], ws, *a[7:], **k), fptq.fptq_w4a4_linear_noalloc):
+        y, acc, _, _ = gpu_linear(x, w, s_w, d, 0.29, entry)
+        assert np.array_equal(acc.cpu().numpy(), acc_ref), (M, N, K)
+        assert np.array_equal(host_bits(y), y_ref), (M, N, K)
+    assert int(ws[: 4 * 1024].max()) == 0

@@ -16,6 +16,17 @@ def test_mfma_probe_counts_and_is_deterministic():
     _, b = probe.mfma_rate(5, 1)
     torch.cuda.synchronize()
     assert torch.equal(a, b) and int((a != 0).sum()) > 60000
+    # the explicit form: fresh operands give a deterministic, non-trivial checksum; the same stream on zeros gives zeros
+    out = torch.empty(131072, dtype=torch.int32, device="cuda")
+    assert probe.mfma_rate_ex(4, 2, 2, out) == 512 * 4 * 4 * 64 * 65536
+    first = out.clone()
+    probe.mfma_rate_ex(4, 2, 2, out)
+    assert torch.equal(first, out) and int((out != 0).sum()) > 120000
+    probe.mfma_rate_ex(4, 3, 1, out)
+    assert int(out[:65536].abs().max()) == 0
+    for bad_args in ((0, 1, 1), (4, 4, 1), (4, 1, 3)):
+        with pytest.raises(probe.ProbeError):
+            probe.mfma_rate_ex(*bad_args, out)
     for bad in (0, -1, (1 << 20) + 1):
         with pytest.raises(probe.ProbeError) as e:
             probe.mfma_rate(bad, 1)
