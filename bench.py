@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--gemm-map", type=int, default=0, choices=(0, 1),
                     help="workgroup -> tile mapping of the prefill kernel: 0 = the library's XCD-aware default, 1 = launch order "
                          "(to measure what the mapping is worth)")
+    ap.add_argument("--gemm-tile", type=int, default=0, choices=range(0, 9),
+                    help="force one tile shape of the prefill kernel (0 = the library's choice): for A/B runs of the launcher's rule")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one elementwise kernel that reads 1 GiB and writes 1 GiB: under rocprofv3 --pmc "
                          "its FETCH_SIZE / WRITE_SIZE readings give the counter scale for a known byte count")
@@ -90,6 +92,7 @@ def main():
     fptq.lib()          # fail loudly if the HIP library is missing
     fptq.fptq_init()
     fptq.fptq_set_gemm_map(args.gemm_map)
+    fptq.fptq_set_gemm_tile(args.gemm_tile)
     dev = torch.device("cuda:0")
 
     def dev_bf16(bits):
@@ -250,7 +253,7 @@ def main():
            "value_dense_int4_activations": dense["step_TOPS"],
            "pct_int8_mfma_peak_dense_int4_activations": round(dense["step_TOPS"] / INT8_MFMA_PEAK_TOPS * 100, 2),
            "warmup_note": "after --warmup steps every region keeps stepping untimed until %.1f s have passed" % args.warm_seconds,
-           "gemm_map": args.gemm_map,
+           "gemm_map": args.gemm_map, "gemm_tile": args.gemm_tile,
            "roofline": roofline}
 
     # ------------------------------------------------------------------ the other prefill configurations, same two regions
