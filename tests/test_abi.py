@@ -97,7 +97,8 @@ def test_testing_knobs_validate_and_the_launch_plan_is_host_arithmetic():
     assert L.fptq_set_gemm_tile(0) == 0 and L.fptq_set_gemm_map(0) == 0
     # the shapes of the benchmark configurations on a 256-CU device: large tiles, two workgroups per CU or one
     plan = fptq.fptq_linear_launch_plan
-    assert plan(8192, 57344, 8192) == ("GemmCfg<2, 2, 4, 2, 3, 2, 1, false>", 224 * 64, 256)
+    assert plan(8192, 57344, 8192) == ("GemmCfg<2, 2, 4, 4, 4, 1, 1, false>", 224 * 32, 256)
+    assert plan(4096, 28672, 4096) == ("GemmCfg<2, 2, 4, 2, 3, 2, 1, false>", 112 * 32, 256)
     assert plan(8192, 8192, 28672) == ("GemmCfg<2, 2, 4, 4, 4, 1, 1, false>", 32 * 32, 256)
     assert plan(2048, 4096, 11008) == ("GemmCfg<2, 2, 4, 2, 3, 1, 2, false>", 16 * 16, 512)
     assert plan(256, 1024, 8192) == ("GemmCfg<1, 1, 2, 2, 4, 1, 4, false>", 64, 256)
