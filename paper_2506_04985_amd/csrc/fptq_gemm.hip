@@ -101,7 +101,7 @@ __device__ inline void load_chunk(__amdgpu_buffer_rsrc_t r, uint8_t *lds_base, i
 }
 
 // Channel scales (and, with a zero point, the weight row sums) of a run of TNE * 32 channels, one or two per lane.
-template <int TNE>
+template <int TNE, bool ZP>
 __device__ inline void load_scales(float (&scv)[(TNE * 32 + 63) / 64], int32_t (&zwv)[(TNE * 32 + 63) / 64],
                                    const float *__restrict__ s_w, const int32_t *__restrict__ wsum, int nw0, int N, int lane)
 {
@@ -109,14 +109,14 @@ __device__ inline void load_scales(float (&scv)[(TNE * 32 + 63) / 64], int32_t (
     for (int i = 0; i < (TNE * 32 + 63) / 64; ++i) {
         const int n = min(nw0 + min(lane + 64 * i, TNE * 32 - 1), N - 1);
         scv[i] = s_w[n];
-        zwv[i] = wsum ? wsum[n] : 0;
+        zwv[i] = ZP ? wsum[n] : 0;
     }
 }
 
 // What a wave does with its finished sub-tiles a[t][i] (t < TNE along n from channel nw0, i < TME along m from
 // token mw0; sub-tile numbers sub0 .. of the wave's TN x TM, counted along n first): the split-K exchange, then
 // the epilogue.
-template <class C, int TNE, int TME, bool ALIGNED, bool DUMP>
+template <class C, int TNE, int TME, bool ALIGNED, bool DUMP, bool ZP>
 __device__ inline void finish(v16i (&a)[TNE][TME], const float (&scv)[(TNE * 32 + 63) / 64],
                               const int32_t (&zwv)[(TNE * 32 + 63) / 64], uint8_t *lds, int wave_all, int wave, int lane,
                               int sub0, int nw0, int mw0, int M, int N, float s_a, const float *__restrict__ d, int zp,
@@ -201,7 +201,7 @@ __device__ inline void finish(v16i (&a)[TNE][TME], const float (&scv)[(TNE * 32 
         const int c = lane + 64 * i;
         if (c < WN) {
             cwbuf[c] = (s_a * scv[i]) * 0.00390625f;
-            if (wsum) zwbuf[c] = (zp * zwv[i]) * 256;
+            if (ZP) zwbuf[c] = (zp * zwv[i]) * 256;
         }
     }
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
@@ -217,7 +217,7 @@ __device__ inline void finish(v16i (&a)[TNE][TME], const float (&scv)[(TNE * 32 
             for (int q = 0; q < 4; ++q) {
                 const float4 c4 = *reinterpret_cast<const float4 *>(cwbuf + tn * 32 + 8 * q + 4 * fg);
                 int32_t a4[4] = {a[tn][tm][4 * q + 0], a[tn][tm][4 * q + 1], a[tn][tm][4 * q + 2], a[tn][tm][4 * q + 3]};
-                if (wsum) {
+                if (ZP) {
                     const int4 z4 = *reinterpret_cast<const int4 *>(zwbuf + tn * 32 + 8 * q + 4 * fg);
                     a4[0] -= z4.x, a4[1] -= z4.y, a4[2] -= z4.z, a4[3] -= z4.w;
                 }
@@ -268,7 +268,9 @@ __device__ inline void finish(v16i (&a)[TNE][TME], const float (&scv)[(TNE * 32 
     }
 }
 
-template <class C, bool ALIGNED, bool DUMP>
+// ZP: the epilogue removes an activation zero point (wsum is then non-null); a separate instance, so that the symmetric
+// grid's epilogue carries neither its code nor its registers (the 256 x 256 instance spilled 13 registers with both in one).
+template <class C, bool ALIGNED, bool DUMP, bool ZP>
 __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const uint8_t *__restrict__ xq, const uint8_t *__restrict__ wq, int M, int N, int ktiles, int tiles_m,
     int tiles_n, float s_a, const float *__restrict__ s_w, const float *__restrict__ d, int zp,
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
     const int fin_nw0 = n0 + (wave_n * C::TN + sub0 % C::TN) * 32, fin_mw0 = m0 + (wave_m * C::TM + sub0 / C::TN) * 32;
     float scv[C::NSC];
     int32_t zwv[C::NSC];
-    if (C::KS > 1) load_scales<C::TNE>(scv, zwv, s_w, wsum, fin_nw0, N, lane);
+    if (C::KS > 1) load_scales<C::TNE, ZP>(scv, zwv, s_w, wsum, fin_nw0, N, lane);
 
     const int steps = (max(kt_end - kt_begin, 0) + C::KS - 1) / C::KS;      // the same for every K group: they share the barriers
 #pragma unroll
@@ -539,11 +541,11 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void linear_mfma_kernel(
         }
         __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
         __builtin_amdgcn_s_barrier();                                // the exchange area is free for the epilogue
-        finish<C, C::TNE, C::TME, ALIGNED, DUMP>(mine, scv, zwv, lds, wave_all, wave, lane, sub0, fin_nw0, fin_mw0, M, N, s_a, d,
+        finish<C, C::TNE, C::TME, ALIGNED, DUMP, ZP>(mine, scv, zwv, lds, wave_all, wave, lane, sub0, fin_nw0, fin_mw0, M, N, s_a, d,
                                                  zp, wsum, y, acc_out, ws, splits, split, pid, total);
     } else {
-        load_scales<C::TN>(scv, zwv, s_w, wsum, fin_nw0, N, lane);
-        finish<C, C::TN, C::TM, ALIGNED, DUMP>(acc, scv, zwv, lds, wave_all, wave, lane, 0, fin_nw0, fin_mw0, M, N, s_a, d, zp,
+        load_scales<C::TN, ZP>(scv, zwv, s_w, wsum, fin_nw0, N, lane);
+        finish<C, C::TN, C::TM, ALIGNED, DUMP, ZP>(acc, scv, zwv, lds, wave_all, wave, lane, 0, fin_nw0, fin_mw0, M, N, s_a, d, zp,
                                                wsum, y, acc_out, ws, splits, split, pid, total);
     }
 }
@@ -555,12 +557,12 @@ void set_gemm_tile(int tile) { g_forced_tile.store(tile, std::memory_order_relax
 void set_gemm_map(int mode) { g_tile_map.store(mode, std::memory_order_relaxed); }
 int forced_gemm_tile() { return g_forced_tile.load(std::memory_order_relaxed); }
 
-template <class C, bool ALIGNED, bool DUMP>
+template <class C, bool ALIGNED, bool DUMP, bool ZP>
 static hipError_t launch_inst(const uint8_t *xq, const uint8_t *wq, int64_t M, int64_t N, int64_t K, float s_a,
                               const float *s_w, const float *d, int zp, const int32_t *wsum, uint16_t *y, int32_t *acc,
                               hipStream_t s, int32_t *ws = nullptr, int splits = 1)
 {
-    auto kern = linear_mfma_kernel<C, ALIGNED, DUMP>;
+    auto kern = linear_mfma_kernel<C, ALIGNED, DUMP, ZP>;
     const DeviceInfo *info;
     hipError_t e0 = device_info(&info);          // sets every instantiation's LDS attribute on the device's first use
     if (e0 != hipSuccess) return e0;
@@ -577,10 +579,16 @@ static hipError_t launch_cfg(const uint8_t *xq, const uint8_t *wq, int64_t M, in
                              hipStream_t s, int32_t *ws = nullptr, int splits = 1)
 {
     const bool aligned = N % 8 == 0;
-    if (acc) return aligned ? launch_inst<C, true, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits)
-                            : launch_inst<C, false, true>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits);
-    return aligned ? launch_inst<C, true, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits)
-                   : launch_inst<C, false, false>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits);
+#define FPTQ_GEMM_INST(A, D, Z) return launch_inst<C, A, D, Z>(xq, wq, M, N, K, s_a, s_w, d, zp, wsum, y, acc, s, ws, splits)
+    if (wsum) {
+        if (acc) { if (aligned) FPTQ_GEMM_INST(true, true, true); FPTQ_GEMM_INST(false, true, true); }
+        if (aligned) FPTQ_GEMM_INST(true, false, true);
+        FPTQ_GEMM_INST(false, false, true);
+    }
+    if (acc) { if (aligned) FPTQ_GEMM_INST(true, true, false); FPTQ_GEMM_INST(false, true, false); }
+    if (aligned) FPTQ_GEMM_INST(true, false, false);
+    FPTQ_GEMM_INST(false, false, false);
+#undef FPTQ_GEMM_INST
 }
 
 // ---- tile shapes (all with 4 waves per K group).  The 256 x 256 tile has the best operand reuse and wins for long
@@ -608,10 +616,10 @@ typedef GemmCfg<1, 1, 2, 2, 4, 1, 4, true> T64x64k4split;
 constexpr int64_t SCRATCH_BYTES = (int64_t)256 * T64x64k4split::ACC_REGS * 64 * 4 + 4096;
 static __device__ __align__(256) int32_t scratch[SCRATCH_BYTES / 4];
 
-template <class C, bool ALIGNED, bool DUMP>
+template <class C, bool ALIGNED, bool DUMP, bool ZP>
 static hipError_t set_lds_attribute()
 {
-    return hipFuncSetAttribute((const void *)linear_mfma_kernel<C, ALIGNED, DUMP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    return hipFuncSetAttribute((const void *)linear_mfma_kernel<C, ALIGNED, DUMP, ZP>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                C::LDS_BYTES);
 }
 
@@ -621,8 +629,10 @@ static hipError_t set_lds_attributes()
     hipError_t e = hipSuccess;
     auto one = [&](hipError_t r) { if (e == hipSuccess) e = r; };
     (void)one;
-    ((one(set_lds_attribute<Cs, true, true>()), one(set_lds_attribute<Cs, true, false>()), one(set_lds_attribute<Cs, false, true>()),
-      one(set_lds_attribute<Cs, false, false>())),
+    ((one(set_lds_attribute<Cs, true, true, false>()), one(set_lds_attribute<Cs, true, false, false>()),
+      one(set_lds_attribute<Cs, false, true, false>()), one(set_lds_attribute<Cs, false, false, false>()),
+      one(set_lds_attribute<Cs, true, true, true>()), one(set_lds_attribute<Cs, true, false, true>()),
+      one(set_lds_attribute<Cs, false, true, true>()), one(set_lds_attribute<Cs, false, false, true>())),
      ...);
     return e;
 }
