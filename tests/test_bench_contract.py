@@ -63,7 +63,8 @@ def test_json_line_has_the_contract_fields():
     # the figure held against the roofline is the lower of the two regions' on the dominant launch
     assert r["achieved"] == min(r["own_activations"]["TOPS"], r["dense_int4_activations"]["TOPS"])
     assert r["ops_per_launch"] == 2 * 8192 * 57344 * 8192
-    assert r["traffic"] is None or r["traffic"] >= 0.95 * r["algorithmic_bytes_per_launch"]
+    assert r["traffic"] is not None and "STALE" not in r["traffic_source"]      # the committed counter table is there and current
+    assert r["traffic"] >= 0.95 * r["algorithmic_bytes_per_launch"]
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"] and c["extrapolated"] is True
     assert "-O3" in c["compiler_flags"]
