@@ -138,3 +138,25 @@ def test_dense_split_k_whole_tensor(oracle, M, N, K):
         assert np.array_equal(acc.cpu().numpy(), acc_ref), (M, N, K)
         assert np.array_equal(host_bits(y), y_ref), (M, N, K)
     assert int(ws[: 4 * 1024].max()) == 0
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 11008, 4096), (2000, 11001, 4100)], ids=["c2 gate", "ragged"])
+def test_every_tile_shape_at_size_dense(oracle, M, N, K):
+    """Every tile shape of the prefill kernel forced on a full-size problem (several rounds of workgroups for the large
+    tiles, thousands of tiles for the small ones, so the tile -> XCD mapping and the partial last round are exercised),
+    dense operands, whole tensor against the oracle.  The ragged case has partial tiles on every edge and a padded last
+    K tile."""
+    x, w, s_w, d = dense_inputs(M, N, K, 6)
+    acc_ref = torch.from_numpy(oracle.gemm_i32(x, w)).cuda()
+    y_ref = torch.from_numpy(oracle.epilogue(acc_ref.cpu().numpy(), np.float32(0.33), s_w, d).view(np.int16)).cuda()
+    xq, wq = fptq.fptq_pack_weights(dev(x)), fptq.fptq_pack_weights(dev(w))
+    s_w_d, d_d = dev(s_w), dev(d)
+    for tile in range(1, 9):
+        fptq.fptq_set_gemm_tile(tile)
+        try:
+            y, acc = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.33, s_w_d, d_d, want_acc=True)
+            y2 = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.33, s_w_d, d_d)
+        finally:
+            fptq.fptq_set_gemm_tile(0)
+        assert torch.equal(acc, acc_ref), (tile, M, N, K)
+        assert torch.equal(y.view(torch.int16), y_ref) and torch.equal(y2.view(torch.int16), y_ref), (tile, M, N, K)
