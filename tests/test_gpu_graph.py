@@ -70,3 +70,33 @@ def test_replays_match_eager_results():
         for k in outputs:
             assert torch.equal(got[k].view(torch.uint8), want[k].view(torch.uint8)), (seed, k)
         assert int(t["ws"][: 4 * 1024].max()) == 0 and junk.isfinite()
+
+
+def test_the_entry_point_that_allocates_nothing_under_capture():
+    """What fptq_w4a4_linear_noalloc is for: a split-K linear captured without any workspace in sight; every replay, on
+    new activations, equals the eager result of the plain entry point."""
+    dev = "cuda"
+    torch.manual_seed(3)
+    M, N, K = 256, 1024, 8192
+    assert fptq.fptq_linear_workspace_bytes(M, N, K) > 0
+    wq = torch.randint(0, 256, (fptq.fptq_packed_bytes(N, K),), dtype=torch.uint8, device=dev)
+    s_w = torch.rand(N, device=dev) * 0.015 + 0.005
+    xq = torch.empty(fptq.fptq_packed_bytes(M, K), dtype=torch.uint8, device=dev)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    fptq.fptq_init()
+    xq.random_(0, 256)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        fptq.fptq_w4a4_linear_noalloc(xq, wq, M, N, K, 0.4, s_w, out=y)
+    for seed in range(4):
+        g = torch.Generator(device=dev).manual_seed(seed)
+        xq.random_(0, 256, generator=g)
+        want = fptq.fptq_w4a4_linear(xq, wq, M, N, K, 0.4, s_w)
+        y.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), want.view(torch.int16)), seed
