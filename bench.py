@@ -465,9 +465,12 @@ def decode_summary(torch, fptq, probe, dev):
     x4 = torch.zeros(1024, dtype=torch.int32, device=dev)
     ceil_us = {name: min(cycled_us(lambda i, ws=ws: probe.read_burst(ws[i], x4, th, ld), len(ws)) for th, ld in ((256, 4), (256, 8), (1024, 4)))
                for name, ws in weights.items()}
+    tiny = torch.zeros(16, dtype=torch.uint8, device=dev)
+    empty_us = graph_time_us(torch, lambda: probe.read_burst(tiny, x4, 256, 1), iters=50, replays=5)      # the launch floor of this replay pattern
     wsum_b = sum(len(ws[0]) for ws in weights.values())
     ceil_layer_us = sum(ceil_us.values())
     res["streaming_read_ceiling"] = {"per_matrix_us": {k: round(v, 2) for k, v in ceil_us.items()}, "layer_us": round(ceil_layer_us, 2),
+                                     "near_empty_kernel_us": round(empty_us, 2),
                                      "GBps": round(wsum_b / ceil_layer_us / 1e3, 1), "pct_hbm_peak": round(wsum_b / ceil_layer_us / 1e3 / HBM_PEAK_GBS * 100, 2),
                                      "what": "a kernel that only reads each matrix's packed bytes (contiguous, one burst of streaming loads, best of three launch "
                                              "shapes), one launch per matrix on cold copies, graph-replayed like the linears"}
