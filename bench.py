@@ -33,7 +33,7 @@ sys.path.insert(0, ROOT)
 INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA, TOP/s
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, GB/s
 TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "linear_mfma_traffic.md")
-CPU_SAMPLE_ROWS = 1024           # token rows of the headline workload the oracle is timed on
+CPU_SAMPLE_ROWS = 4096           # token rows of the headline workload the oracle is timed on
 WARM_SECONDS = 1.0               # untimed stepping before each timed region, beyond --warmup (clock and power settle)
 
 
