@@ -78,17 +78,6 @@ int device_cus_or_default();                     // compute units of the current
 hipError_t gemm_device_init(DeviceInfo *info);
 hipError_t hadamard_device_init(int device);
 
-// Once-per-device guard for a kernel's function attribute: bit d of `done` is set when device d has it.
-// Setting it twice is harmless, so a race between two first callers needs no lock.
-#define FPTQ_ONCE_PER_DEVICE(done, device, call)                                             \
-    do {                                                                                     \
-        if (!((done).load(std::memory_order_acquire) >> (device) & 1)) {                     \
-            hipError_t e_ = (call);                                                          \
-            if (e_ != hipSuccess) return e_;                                                 \
-            (done).fetch_or((uint64_t)1 << (device), std::memory_order_release);            \
-        }                                                                                    \
-    } while (0)
-
 // fp32 -> bf16 bit pattern, round to nearest even (NaN stays a quiet NaN)
 __device__ inline uint16_t bf16_rne(float f)
 {
